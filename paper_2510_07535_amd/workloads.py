@@ -1,0 +1,307 @@
+"""Seeded synthetic inputs for the verify-step attention path.
+
+This module only *draws data*: random q/k/v values, draft trees, context
+lengths and page permutations.  It contains none of the method's arithmetic
+(no scores, no softmax, no masks) and imports neither the HIP binding nor the
+CPU oracle, so both sides can be fed the very same buffers.
+
+The paper measures on LongSpecBench (Sec. 3.1: 200 real conversations with
+4K-64K-token inputs) with Llama-3.1-8B / Llama-3.3-70B targets and a 60-node
+draft tree (Appendix A.1).  None of that data is reproduced here; the cases
+below only take its *shapes*: the context-length range (extended to the 128K
+limit named in Sec. 1), the public head shapes of the two target models, and
+the tree sizes.  Values are N(0,1).
+
+Conventions shared by every consumer of a ``Case``:
+  * q          [B, N, Hq, D]      draft-token queries (already position-encoded)
+  * k_pool     [pages, Hkv, 16, D] paged key cache, v_pool alike
+  * page_table [B, max_pages]     physical page of logical page p; -1 = unused
+  * ctx_lens   [B]                prefix length L_b, *excluding* the N drafts
+  * tree_parent[B, N]             -1 = root, else index of an earlier node
+  * draft node j of sequence b has its K/V row at logical position L_b + j
+bf16 tensors are carried as uint16 bit patterns (numpy has no bf16).
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+from typing import Optional, Sequence
+
+import numpy as np
+
+PAGE = 16
+
+DT_BF16 = 0
+DT_F32 = 1
+DT_F16 = 2
+
+
+# ----------------------------------------------------------------------------
+# storage helpers (format conversion only)
+# ----------------------------------------------------------------------------
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even float32 -> bfloat16, returned as uint16 bits."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def store(x_f32: np.ndarray, dtype: int) -> np.ndarray:
+    if dtype == DT_BF16:
+        return f32_to_bf16_bits(x_f32)
+    if dtype == DT_F16:
+        return x_f32.astype(np.float16).view(np.uint16)
+    return np.ascontiguousarray(x_f32, dtype=np.float32)
+
+
+def widen(x: np.ndarray, dtype: int) -> np.ndarray:
+    """Stored tensor -> float64 (exact)."""
+    if dtype == DT_BF16:
+        return bf16_bits_to_f32(x).astype(np.float64)
+    if dtype == DT_F16:
+        return x.view(np.float16).astype(np.float64)
+    return x.astype(np.float64)
+
+
+# ----------------------------------------------------------------------------
+# draft-tree shapes
+# ----------------------------------------------------------------------------
+def chain_tree(n: int) -> np.ndarray:
+    """Sequence (non-tree) verify: node i follows node i-1."""
+    return np.arange(-1, n - 1, dtype=np.int32)
+
+
+def node_depths(parent: Sequence[int]) -> np.ndarray:
+    """Depth with the root counted as 1 (a chain of n nodes has depth n)."""
+    d = np.zeros(len(parent), dtype=np.int32)
+    for i, p in enumerate(parent):
+        d[i] = 1 if p < 0 else d[p] + 1
+    return d
+
+
+def random_tree(n: int, max_depth: Optional[int], rng: np.random.Generator) -> np.ndarray:
+    """Node 0 is the root; every later node draws its parent uniformly from
+    the earlier nodes whose depth is below ``max_depth`` (root depth = 1)."""
+    parent = np.full(n, -1, dtype=np.int32)
+    depth = np.zeros(n, dtype=np.int32)
+    depth[0] = 1
+    for i in range(1, n):
+        if max_depth is None:
+            cand = np.arange(i)
+        else:
+            cand = np.nonzero(depth[:i] <= max_depth - 1)[0]
+        p = int(cand[rng.integers(0, len(cand))])
+        parent[i] = p
+        depth[i] = depth[p] + 1
+    return parent
+
+
+def hybrid_tree(n_tree: int, n_chain: int, rng: np.random.Generator) -> np.ndarray:
+    """A random tree with a chain hung off its deepest leaf (lowest index on
+    ties); the chain nodes take the indices after the tree's."""
+    t = random_tree(n_tree, None, rng)
+    d = node_depths(t)
+    leaf = int(np.argmax(d))  # argmax returns the first maximal entry
+    chain = np.arange(n_tree - 1, n_tree + n_chain - 1, dtype=np.int32)
+    chain[0] = leaf
+    return np.concatenate([t, chain]).astype(np.int32)
+
+
+def spec_tree(parent: Sequence[int]) -> np.ndarray:
+    """Sec. 3.2.2 decode stage: one extra leaf per node, following that node's
+    root path; leaf k (index n+k) hangs off node k."""
+    n = len(parent)
+    return np.concatenate([np.asarray(parent, np.int32), np.arange(n, dtype=np.int32)])
+
+
+# ----------------------------------------------------------------------------
+# the case container
+# ----------------------------------------------------------------------------
+@dataclasses.dataclass
+class Case:
+    name: str
+    seed: int
+    dtype: int
+    B: int
+    N: int
+    Hq: int
+    Hkv: int
+    D: int
+    scale: float                 # already rounded to float32
+    q: np.ndarray
+    k_pool: np.ndarray
+    v_pool: np.ndarray
+    page_table: Optional[np.ndarray]   # None => identity paging
+    ctx_lens: np.ndarray
+    tree_parent: np.ndarray
+    max_pages_per_seq: int
+    stride_page: int
+    stride_head: int
+    stride_token: int
+    n_pool_pages: int
+
+    @property
+    def G(self) -> int:
+        return self.Hq // self.Hkv
+
+    @property
+    def max_ctx_len(self) -> int:
+        return int(self.ctx_lens.max()) if self.B else 0
+
+    def kv_bytes(self) -> int:
+        """K+V bytes of every visible-or-not cached row the step has to scan:
+        sum_b (L_b + N) * Hkv * D * 2 tensors * element size."""
+        esz = 4 if self.dtype == DT_F32 else 2
+        return int((self.ctx_lens.astype(np.int64) + self.N).sum()) * self.Hkv * self.D * 2 * esz
+
+
+def _normal(rng: np.random.Generator, shape) -> np.ndarray:
+    return rng.standard_normal(size=shape, dtype=np.float32)
+
+
+def make_case(
+    name: str,
+    seed: int,
+    *,
+    dtype: int,
+    Hq: int,
+    Hkv: int,
+    D: int,
+    ctx_lens: Sequence[int],
+    trees: Sequence[np.ndarray],
+    paged: bool = True,
+    head_major: bool = True,
+    outlier_frac: float = 0.0,
+    outlier_gain: float = 8.0,
+    spare_pages: int = 0,
+    scale: Optional[float] = None,
+) -> Case:
+    """Build one verify step.  ``trees`` holds one parent array per sequence
+    (all of the same length N).  With ``paged`` the logical pages of all
+    sequences are scattered over one shared pool by a seeded permutation;
+    otherwise sequence b owns a contiguous run of pages and page_table is
+    None when B == 1.  ``head_major`` picks [page][Hkv][16][D] over
+    [page][16][Hkv][D] (the latter is a plain [token][Hkv][D] array when the
+    pages are in order)."""
+    rng = np.random.Generator(np.random.Philox(key=seed))            # values
+    prng = np.random.Generator(np.random.Philox(key=seed ^ 0x9A6E))  # page order only
+    B = len(ctx_lens)
+    N = len(trees[0])
+    assert all(len(t) == N for t in trees) and len(trees) == B
+    ctx = np.asarray(ctx_lens, dtype=np.int32)
+    pages_per_seq = [(int(L) + N + PAGE - 1) // PAGE for L in ctx]
+    max_pages = max(pages_per_seq) if B else 0
+    total_pages = sum(pages_per_seq) + spare_pages
+
+    if paged:
+        perm = prng.permutation(total_pages).astype(np.int32)
+    else:
+        perm = np.arange(total_pages, dtype=np.int32)
+    page_table = np.full((B, max(max_pages, 1)), -1, dtype=np.int32)
+    o = 0
+    for b in range(B):
+        page_table[b, : pages_per_seq[b]] = perm[o : o + pages_per_seq[b]]
+        o += pages_per_seq[b]
+
+    sdtype = np.float32 if dtype == DT_F32 else np.uint16
+    if head_major:
+        pool_shape = (max(total_pages, 1), Hkv, PAGE, D)
+        stride_page, stride_head, stride_token = Hkv * PAGE * D, PAGE * D, D
+    else:
+        pool_shape = (max(total_pages, 1), PAGE, Hkv, D)
+        stride_page, stride_head, stride_token = PAGE * Hkv * D, D, Hkv * D
+    # unused slots (page padding, spare pages) keep a recognisable filler so a
+    # wrong gather shows up as a large error rather than as a near miss
+    filler = store(np.full((1,), 977.0, np.float32), dtype)[0]
+    k_pool = np.full(pool_shape, filler, dtype=sdtype)
+    v_pool = np.full(pool_shape, filler, dtype=sdtype)
+
+    q = store(_normal(rng, (B, N, Hq, D)), dtype)
+    for b in range(B):
+        T = int(ctx[b]) + N
+        if T == 0:
+            continue
+        k = _normal(rng, (T, Hkv, D))
+        v = _normal(rng, (T, Hkv, D))
+        if outlier_frac > 0.0:
+            hot = rng.random(int(ctx[b])) < outlier_frac   # prefix positions only
+            k[: int(ctx[b])][hot] *= np.float32(outlier_gain)
+        npg = pages_per_seq[b]
+        pad = npg * PAGE - T
+        for src, pool in ((k, k_pool), (v, v_pool)):
+            s = store(src, dtype)
+            if pad:
+                s = np.concatenate([s, np.full((pad, Hkv, D), filler, dtype=sdtype)], axis=0)
+            s = s.reshape(npg, PAGE, Hkv, D)
+            if head_major:
+                s = s.transpose(0, 2, 1, 3)
+            pool[page_table[b, :npg]] = s
+        del k, v
+
+    if scale is None:
+        scale = 1.0 / math.sqrt(D)
+    scale = float(np.float32(scale))
+    pt: Optional[np.ndarray] = page_table
+    if not paged and B == 1:
+        pt = None
+    return Case(
+        name=name, seed=seed, dtype=dtype, B=B, N=N, Hq=Hq, Hkv=Hkv, D=D, scale=scale,
+        q=q, k_pool=k_pool, v_pool=v_pool, page_table=pt, ctx_lens=ctx,
+        tree_parent=np.stack([np.asarray(t, np.int32) for t in trees]).astype(np.int32),
+        max_pages_per_seq=page_table.shape[1],
+        stride_page=stride_page, stride_head=stride_head, stride_token=stride_token,
+        n_pool_pages=pool_shape[0],
+    )
+
+
+# ----------------------------------------------------------------------------
+# the five named configurations
+# ----------------------------------------------------------------------------
+CONFIG_NAMES = ("tiny_chain4_f32", "8b_chain6_32k", "8b_tree60_64k", "70b_hybrid40_128k", "8b_batch16_tree26")
+
+
+def config_ctx_lens(idx: int, seed: Optional[int] = None) -> np.ndarray:
+    """Context lengths of configuration ``idx`` (0-based) without building it."""
+    seed = idx + 1 if seed is None else seed
+    if idx == 0:
+        return np.array([512], np.int32)
+    if idx == 1:
+        return np.array([32768], np.int32)
+    if idx == 2:
+        return np.array([65536], np.int32)
+    if idx == 3:
+        return np.array([131072], np.int32)
+    if idx == 4:
+        r = np.random.Generator(np.random.Philox(key=seed ^ 0x5EED))
+        return r.integers(8192, 65536, size=16, endpoint=True).astype(np.int32)
+    raise ValueError(idx)
+
+
+def make_config(idx: int, seed: Optional[int] = None, ctx_scale: float = 1.0) -> Case:
+    """Configuration ``idx`` (0-based, in the order of the benchmark list).
+    ``ctx_scale`` < 1 shrinks every context length by that factor (kept for
+    CPU-sized parity runs of the same structure); 1.0 is the named size."""
+    seed = idx + 1 if seed is None else seed
+    trng = np.random.Generator(np.random.Philox(key=seed ^ 0x7EE))
+    ctx = np.maximum(1, (config_ctx_lens(idx, seed).astype(np.float64) * ctx_scale).astype(np.int64))
+    name = CONFIG_NAMES[idx] + ("" if ctx_scale == 1.0 else f"@{ctx_scale:g}")
+    if idx == 0:
+        return make_case(name, seed, dtype=DT_F32, Hq=4, Hkv=1, D=64, ctx_lens=ctx,
+                         trees=[chain_tree(4)], paged=False, head_major=False)
+    if idx == 1:
+        return make_case(name, seed, dtype=DT_BF16, Hq=32, Hkv=8, D=128, ctx_lens=ctx,
+                         trees=[chain_tree(6)])
+    if idx == 2:
+        return make_case(name, seed, dtype=DT_BF16, Hq=32, Hkv=8, D=128, ctx_lens=ctx,
+                         trees=[random_tree(60, 6, trng)])
+    if idx == 3:
+        return make_case(name, seed, dtype=DT_BF16, Hq=64, Hkv=8, D=128, ctx_lens=ctx,
+                         trees=[hybrid_tree(32, 8, trng)], outlier_frac=0.05)
+    if idx == 4:
+        return make_case(name, seed, dtype=DT_BF16, Hq=32, Hkv=8, D=128, ctx_lens=ctx,
+                         trees=[random_tree(26, 5, trng) for _ in range(len(ctx))])
+    raise ValueError(idx)
