@@ -1,0 +1,184 @@
+/*
+ * owl.h -- C ABI of the MI355X (gfx950) verify-step attention library.
+ *
+ * The operation is the attention sub-step of the target model's verification
+ * forward pass in tree / sequence speculative decoding: N drafted tokens (a
+ * chain, or a token tree) of each sequence attend over that sequence's long
+ * prefix KV cache plus the drafted tokens on their own root path.
+ *
+ * Where the paper defines it:
+ *   - Sec. 1 / Sec. 2: the target model verifies all drafted tokens in one
+ *     parallel pass whose cost, in the memory-bound regime, is the scan of the
+ *     cached context.
+ *   - Sec. 3.2.2 "Decode Stage" and Algorithm 1 (Prepare / OurTreeVerify): a
+ *     token placed after a tree path sees exactly that path; realised by
+ *     "manipulating the attention mask".  The example there fixes the rule:
+ *     ancestor-or-self visibility among the drafts, full visibility of the
+ *     prefix.
+ *   - Sec. 3.2.3 / Algorithm 1 (NonTreeVerify): sequence verification is the
+ *     chain-shaped tree.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers unless the name ends in _host.
+ *   - The caller owns every buffer, the workspace included.  No entry point
+ *     allocates or frees device memory, and none synchronises: work is
+ *     enqueued on `stream` (a hipStream_t passed as void*, NULL = the default
+ *     stream) and the call returns.
+ *   - Errors the host can see (null pointers, unsupported shapes, a workspace
+ *     that is too small) give a negative owl_status before anything is
+ *     launched.  Errors that live in device-resident arrays (a parent index
+ *     out of order, a page id outside the pool, a context longer than
+ *     announced) cannot be seen without a synchronisation; the kernels never
+ *     follow such a value out of bounds, they neutralise it (a bad parent
+ *     counts as a root, a bad page reads page 0, a bad length is clamped) and
+ *     OR a bit into *dev_status if that pointer is not NULL.  `out` of the
+ *     affected sequence is then unspecified.
+ */
+#ifndef OWL_H_
+#define OWL_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum owl_status {
+    OWL_OK = 0,
+    OWL_ERR_INVALID_ARG = -1,    /* null pointer, non-positive size, Hq % Hkv != 0 ...  */
+    OWL_ERR_BAD_TREE = -2,       /* parent[i] outside {-1} u [0, i)   (host variant)    */
+    OWL_ERR_TOO_MANY_DRAFT = -3, /* n_draft > 64: one 64-bit word holds a node's mask   */
+    OWL_ERR_UNSUPPORTED = -4,    /* head_dim, page_size or dtype this build lacks       */
+    OWL_ERR_WORKSPACE = -5,      /* workspace_bytes below owl_verify_attn_workspace_size */
+    OWL_ERR_HIP = -6             /* a HIP runtime call failed (launch, attribute query) */
+} owl_status;
+
+typedef enum owl_dtype {
+    OWL_BF16 = 0,   /* bf16 storage, bf16 MFMA, fp32 accumulate and softmax */
+    OWL_F32 = 1,    /* fp32 storage and arithmetic (small correctness shape) */
+    OWL_F16 = 2     /* fp16 storage (the paper's inference type, App. A.1), fp16 MFMA */
+} owl_dtype;
+
+/* bits OR-ed into *dev_status */
+#define OWL_DEV_BAD_PARENT 1u   /* some parent[i] not in {-1} u [0, i)            */
+#define OWL_DEV_BAD_PAGE 2u     /* a needed page id not in [0, n_pool_pages)      */
+#define OWL_DEV_BAD_CTX_LEN 4u  /* some ctx_lens[b] not in [0, max_ctx_len]       */
+
+/*
+ * Shape of one verify step.  Strides are in ELEMENTS of qkv_dtype.
+ * The element (page p, kv head g, slot s, channel d) of a cache lives at
+ *     p * kv_stride_page + g * kv_stride_head + s * kv_stride_token + d ,
+ * channels contiguous.  [page][Hkv][16][D] ("head-major": each (page, head) is
+ * one contiguous 16*D run, the layout the kernels stream best) and
+ * [page][16][Hkv][D] (a plain [token][Hkv][D] array when pages are in order)
+ * are both expressible.  Byte offsets of the strides must be multiples of 16.
+ */
+typedef struct owl_verify_desc {
+    int32_t batch;              /* B >= 1 sequences                                      */
+    int32_t n_draft;            /* N in [1, 64] drafted tokens per sequence              */
+    int32_t n_q_heads;          /* Hq                                                    */
+    int32_t n_kv_heads;         /* Hkv, divides Hq; query head h reads kv head h/(Hq/Hkv) */
+    int32_t head_dim;           /* D: 64 or 128                                          */
+    int32_t page_size;          /* tokens per page: 16                                   */
+    int32_t max_pages_per_seq;  /* row length of page_table                              */
+    int32_t max_ctx_len;        /* upper bound of ctx_lens[]; sizes the split plan       */
+    int32_t qkv_dtype;          /* owl_dtype of q, k_cache, v_cache                      */
+    int32_t split_tokens;       /* 0 = let the library choose; else tokens per KV split  */
+                                /* (rounded up to a multiple of 64) -- testing / tuning  */
+    float scale;                /* multiplies q.k before the softmax, e.g. 1/sqrt(D)     */
+    int32_t reserved_;          /* set to 0                                              */
+    int64_t kv_stride_page, kv_stride_head, kv_stride_token;
+    int64_t n_pool_pages;       /* pages in k_cache / v_cache (bounds for page ids)      */
+} owl_verify_desc;
+
+/* What the library decided for a descriptor; informational (bench, tests). */
+typedef struct owl_plan {
+    int32_t split_tokens;    /* tokens of the logical sequence (prefix + drafts) per split */
+    int32_t max_splits;      /* splits of the longest admissible sequence                  */
+    int32_t rows_per_kv;     /* R = (Hq/Hkv) * N query rows packed against one KV stream   */
+    int32_t row_tiles;       /* 16-row MFMA tiles covering R                               */
+    int32_t row_groups;      /* workgroups sharing one KV split, each owning some tiles    */
+    int32_t tiles_per_wave;  /* row tiles held in one wavefront's accumulators             */
+    int32_t kernel_variant;  /* internal id of the instantiated split-KV kernel            */
+    int32_t n_workgroups;    /* grid size of the split-KV pass                             */
+    size_t workspace_bytes;
+} owl_plan;
+
+/* Fill *plan for `desc` on the current device.  Host only, no launch. */
+owl_status owl_verify_attn_plan(const owl_verify_desc *desc, owl_plan *plan);
+
+/* Bytes of device scratch owl_verify_attn needs for `desc` (split partials). */
+owl_status owl_verify_attn_workspace_size(const owl_verify_desc *desc, size_t *bytes);
+
+/*
+ * The verify-step attention (Sec. 3.2.2 Decode Stage; Algorithm 1,
+ * OurTreeVerify / NonTreeVerify).  For every sequence b, draft node i and
+ * query head h, with g = h / (Hq/Hkv) and L = ctx_lens[b]:
+ *     keys    = logical positions 0..L-1  and  L + j for every j on the root
+ *               path of i (i itself included)
+ *     out[b,i,h,:] = softmax_over_keys(scale * q[b,i,h,:] . K[key,g,:]) @ V[key,g,:]
+ * Logical position p of sequence b is slot p % 16 of physical page
+ * page_table[b][p / 16]; the drafts' own K/V rows must already be in the
+ * cache at positions L .. L+N-1, so page_table must cover L + N positions.
+ *
+ *   q            [B][N][Hq][D]  qkv_dtype, contiguous
+ *   k_cache, v_cache             paged pools, see owl_verify_desc
+ *   page_table   [B][max_pages_per_seq] int32, or NULL = identity (page p of
+ *                every sequence is physical page p; only sensible for B == 1)
+ *   ctx_lens     [B] int32, prefix lengths, drafts not counted, 0 allowed
+ *   tree_parent  [B][N] int32, -1 = root, else an index < i
+ *   out          [B][N][Hq][D] float32, contiguous, fully overwritten
+ *   workspace    >= owl_verify_attn_workspace_size() bytes, 256-byte aligned;
+ *                contents need no initialisation and are garbage afterwards
+ *   dev_status   optional uint32 on the device, OR-ed with OWL_DEV_* bits;
+ *                the caller zeroes and reads it
+ * Calls that share a workspace must be ordered on one stream.
+ */
+owl_status owl_verify_attn(const owl_verify_desc *desc, const void *q, const void *k_cache,
+                           const void *v_cache, const int32_t *page_table,
+                           const int32_t *ctx_lens, const int32_t *tree_parent, float *out,
+                           void *workspace, size_t workspace_bytes, uint32_t *dev_status,
+                           void *stream);
+
+/*
+ * The attention mask of a drafted tree in packed form (Sec. 3.2.2: "manipulating
+ * the position ids and attention mask"; Algorithm 1, Prepare): for every
+ * sequence b and node i,
+ *     anc_mask[b][i]  bit j set  <=>  node j is on the path from i to its root,
+ *                                     i itself included
+ *     depth[b][i]     number of nodes on that path (root = 1); the position id
+ *                     of node i is then ctx_lens[b] + depth - 1.  May be NULL.
+ * tree_parent [B][N] int32 device; anc_mask [B][N] uint64 device; depth [B][N]
+ * int32 device.  This is the same routine owl_verify_attn runs internally.
+ */
+owl_status owl_build_tree_mask(const int32_t *tree_parent, int32_t batch, int32_t n_draft,
+                               uint64_t *anc_mask, int32_t *depth, uint32_t *dev_status,
+                               void *stream);
+
+/* Host twin of owl_build_tree_mask for one tree; all pointers are HOST memory.
+ * Validates the tree: OWL_ERR_BAD_TREE if some parent[i] is not in {-1} u [0,i). */
+owl_status owl_build_tree_mask_host(const int32_t *tree_parent_host, int32_t n_draft,
+                                    uint64_t *anc_mask_host, int32_t *depth_host);
+
+/*
+ * Paging on its own (the logical -> physical walk owl_verify_attn performs,
+ * exposed so it can be checked bit for bit): copies n_tokens rows of sequence
+ * `seq`, starting at logical position first_pos, of `cache` (K or V) into
+ * dst[n_tokens][Hkv][D] in qkv_dtype.  Uses batch, n_kv_heads, head_dim,
+ * page_size, max_pages_per_seq, qkv_dtype, strides and n_pool_pages of desc.
+ */
+owl_status owl_gather_kv(const owl_verify_desc *desc, const void *cache,
+                         const int32_t *page_table, int32_t seq, int64_t first_pos,
+                         int64_t n_tokens, void *dst, uint32_t *dev_status, void *stream);
+
+/* Static string for a status code. */
+const char *owl_status_str(owl_status s);
+
+/* Library version, "major.minor". */
+const char *owl_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OWL_H_ */

@@ -1,0 +1,176 @@
+"""Thin ctypes binding of libowl.so: argument marshalling only.
+
+Every step of the verify-attention path runs inside the library's HIP kernels;
+torch is used here for nothing but device pointers and the current stream.
+There is no CPU fallback: a missing library is an ImportError-like failure.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libowl.so")
+
+OWL_BF16, OWL_F32, OWL_F16 = 0, 1, 2
+OWL_OK = 0
+OWL_ERR_INVALID_ARG, OWL_ERR_BAD_TREE, OWL_ERR_TOO_MANY_DRAFT = -1, -2, -3
+OWL_ERR_UNSUPPORTED, OWL_ERR_WORKSPACE, OWL_ERR_HIP = -4, -5, -6
+OWL_DEV_BAD_PARENT, OWL_DEV_BAD_PAGE, OWL_DEV_BAD_CTX_LEN = 1, 2, 4
+
+EXPORTS = (
+    "owl_verify_attn_plan", "owl_verify_attn_workspace_size", "owl_verify_attn",
+    "owl_build_tree_mask", "owl_build_tree_mask_host", "owl_gather_kv",
+    "owl_status_str", "owl_version",
+)
+
+
+class VerifyDesc(ctypes.Structure):
+    """Mirror of owl_verify_desc (include/owl.h)."""
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("n_draft", ctypes.c_int32),
+        ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("page_size", ctypes.c_int32),
+        ("max_pages_per_seq", ctypes.c_int32), ("max_ctx_len", ctypes.c_int32),
+        ("qkv_dtype", ctypes.c_int32), ("split_tokens", ctypes.c_int32),
+        ("scale", ctypes.c_float), ("reserved_", ctypes.c_int32),
+        ("kv_stride_page", ctypes.c_int64), ("kv_stride_head", ctypes.c_int64),
+        ("kv_stride_token", ctypes.c_int64), ("n_pool_pages", ctypes.c_int64),
+    ]
+
+
+class Plan(ctypes.Structure):
+    """Mirror of owl_plan."""
+    _fields_ = [
+        ("split_tokens", ctypes.c_int32), ("max_splits", ctypes.c_int32),
+        ("rows_per_kv", ctypes.c_int32), ("row_tiles", ctypes.c_int32),
+        ("row_groups", ctypes.c_int32), ("tiles_per_wave", ctypes.c_int32),
+        ("kernel_variant", ctypes.c_int32), ("n_workgroups", ctypes.c_int32),
+        ("workspace_bytes", ctypes.c_size_t),
+    ]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class OwlError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {status_str(code)} ({code})")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2510_07535_amd.build` "
+                "(there is no fallback path)")
+        l = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        l.owl_verify_attn_plan.restype = ctypes.c_int
+        l.owl_verify_attn_plan.argtypes = [ctypes.POINTER(VerifyDesc), ctypes.POINTER(Plan)]
+        l.owl_verify_attn_workspace_size.restype = ctypes.c_int
+        l.owl_verify_attn_workspace_size.argtypes = [ctypes.POINTER(VerifyDesc),
+                                                     ctypes.POINTER(ctypes.c_size_t)]
+        l.owl_verify_attn.restype = ctypes.c_int
+        l.owl_verify_attn.argtypes = [ctypes.POINTER(VerifyDesc), vp, vp, vp, vp, vp, vp, vp,
+                                      vp, ctypes.c_size_t, vp, vp]
+        l.owl_build_tree_mask.restype = ctypes.c_int
+        l.owl_build_tree_mask.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+        l.owl_build_tree_mask_host.restype = ctypes.c_int
+        l.owl_build_tree_mask_host.argtypes = [vp, i32, vp, vp]
+        l.owl_gather_kv.restype = ctypes.c_int
+        l.owl_gather_kv.argtypes = [ctypes.POINTER(VerifyDesc), vp, vp, i32, i64, i64, vp, vp, vp]
+        l.owl_status_str.restype = ctypes.c_char_p
+        l.owl_status_str.argtypes = [ctypes.c_int]
+        l.owl_version.restype = ctypes.c_char_p
+        _lib = l
+    return _lib
+
+
+def status_str(code: int) -> str:
+    return lib().owl_status_str(int(code)).decode()
+
+
+def _check(code: int, what: str) -> None:
+    if code != OWL_OK:
+        raise OwlError(code, what)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _stream() -> int:
+    import torch
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def make_desc(*, batch, n_draft, n_q_heads, n_kv_heads, head_dim, max_pages_per_seq, max_ctx_len,
+              qkv_dtype, scale, kv_stride_page, kv_stride_head, kv_stride_token, n_pool_pages,
+              page_size=16, split_tokens=0) -> VerifyDesc:
+    return VerifyDesc(batch=batch, n_draft=n_draft, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads,
+                      head_dim=head_dim, page_size=page_size, max_pages_per_seq=max_pages_per_seq,
+                      max_ctx_len=max_ctx_len, qkv_dtype=qkv_dtype, split_tokens=split_tokens,
+                      scale=scale, reserved_=0, kv_stride_page=kv_stride_page,
+                      kv_stride_head=kv_stride_head, kv_stride_token=kv_stride_token,
+                      n_pool_pages=n_pool_pages)
+
+
+def owl_verify_attn_plan(desc: VerifyDesc) -> Plan:
+    plan = Plan()
+    _check(lib().owl_verify_attn_plan(ctypes.byref(desc), ctypes.byref(plan)), "owl_verify_attn_plan")
+    return plan
+
+
+def owl_verify_attn_workspace_size(desc: VerifyDesc) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().owl_verify_attn_workspace_size(ctypes.byref(desc), ctypes.byref(n)),
+           "owl_verify_attn_workspace_size")
+    return int(n.value)
+
+
+def owl_verify_attn(desc: VerifyDesc, q, k_cache, v_cache, page_table, ctx_lens, tree_parent, out,
+                    workspace, dev_status=None, stream: Optional[int] = None) -> None:
+    """All tensor arguments are torch CUDA tensors (or None where the C ABI
+    allows NULL); nothing is copied or allocated here."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().owl_verify_attn(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                               _ptr(page_table), _ptr(ctx_lens), _ptr(tree_parent), _ptr(out),
+                               _ptr(workspace), ws_bytes, _ptr(dev_status),
+                               _stream() if stream is None else stream)
+    _check(rc, "owl_verify_attn")
+
+
+def owl_build_tree_mask(tree_parent, anc_mask, depth=None, dev_status=None,
+                        stream: Optional[int] = None) -> None:
+    B, N = tree_parent.shape
+    rc = lib().owl_build_tree_mask(_ptr(tree_parent), B, N, _ptr(anc_mask), _ptr(depth),
+                                   _ptr(dev_status), _stream() if stream is None else stream)
+    _check(rc, "owl_build_tree_mask")
+
+
+def owl_build_tree_mask_host(parent):
+    """numpy int32 [N] -> (anc uint64 [N], depth int32 [N]); raises OwlError on a bad tree."""
+    import numpy as np
+    par = np.ascontiguousarray(parent, dtype=np.int32)
+    n = int(par.shape[0])
+    anc = np.zeros(max(n, 1), dtype=np.uint64)
+    depth = np.zeros(max(n, 1), dtype=np.int32)
+    rc = lib().owl_build_tree_mask_host(par.ctypes.data, n, anc.ctypes.data, depth.ctypes.data)
+    _check(rc, "owl_build_tree_mask_host")
+    return anc[:n], depth[:n]
+
+
+def owl_gather_kv(desc: VerifyDesc, cache, page_table, seq: int, first_pos: int, n_tokens: int, dst,
+                  dev_status=None, stream: Optional[int] = None) -> None:
+    rc = lib().owl_gather_kv(ctypes.byref(desc), _ptr(cache), _ptr(page_table), seq, first_pos,
+                             n_tokens, _ptr(dst), _ptr(dev_status),
+                             _stream() if stream is None else stream)
+    _check(rc, "owl_gather_kv")

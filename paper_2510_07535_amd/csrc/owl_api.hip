@@ -1,0 +1,277 @@
+// Host side of the C ABI: argument checks, the split plan, kernel launches.
+#include <math.h>
+#include <string.h>
+
+#include <mutex>
+
+#include "owl_internal.h"
+
+using namespace owl;
+
+namespace {
+
+int elem_size(int dtype) { return dtype == OWL_F32 ? 4 : 2; }
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Compute units of the current device; 256 (an MI355X) when no device answers,
+// so that planning stays usable for host-only checks.
+int device_cus()
+{
+    static int cached[16] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
+
+owl_status check_desc(const owl_verify_desc *d)
+{
+    if (!d) return OWL_ERR_INVALID_ARG;
+    if (d->batch < 1 || d->n_draft < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1) return OWL_ERR_INVALID_ARG;
+    if (d->n_draft > 64) return OWL_ERR_TOO_MANY_DRAFT;
+    if (d->n_q_heads % d->n_kv_heads) return OWL_ERR_INVALID_ARG;
+    if (d->qkv_dtype != OWL_BF16 && d->qkv_dtype != OWL_F32 && d->qkv_dtype != OWL_F16) return OWL_ERR_UNSUPPORTED;
+    if (d->head_dim != 64 && d->head_dim != 128) return OWL_ERR_UNSUPPORTED;
+    if (d->page_size != kPage) return OWL_ERR_UNSUPPORTED;
+    if (d->max_ctx_len < 0 || d->max_ctx_len > (1 << 30)) return OWL_ERR_INVALID_ARG;
+    if (d->max_pages_per_seq < 0 || d->n_pool_pages < 1) return OWL_ERR_INVALID_ARG;
+    if (d->split_tokens < 0) return OWL_ERR_INVALID_ARG;
+    if (!(d->scale > 0.0f) || !isfinite(d->scale)) return OWL_ERR_INVALID_ARG;
+    const int es = elem_size(d->qkv_dtype);
+    const int64_t st[3] = {d->kv_stride_page, d->kv_stride_head, d->kv_stride_token};
+    for (int64_t s : st)
+        if (s < 0 || (s * es) % 16 != 0) return OWL_ERR_INVALID_ARG;
+    if (d->kv_stride_token < d->head_dim) return OWL_ERR_INVALID_ARG;
+    if ((int64_t)d->n_q_heads / d->n_kv_heads * d->n_draft > 64 * 64) return OWL_ERR_UNSUPPORTED;
+    return OWL_OK;
+}
+
+struct FullPlan {
+    owl_plan pub;
+    const Variant *variant;
+    size_t part_o_bytes, part_ml_bytes;
+};
+
+owl_status make_plan(const owl_verify_desc *d, FullPlan *fp)
+{
+    owl_status st = check_desc(d);
+    if (st != OWL_OK) return st;
+    const int G = d->n_q_heads / d->n_kv_heads;
+    const int R = G * d->n_draft;
+    const int RT = (R + kRowTile - 1) / kRowTile;
+    int tpw, wr, wk, rgs;
+    if (d->qkv_dtype == OWL_F32) {
+        tpw = 1; wr = 4; wk = 1; rgs = (RT + 3) / 4;
+    } else if (RT <= 2) {
+        tpw = RT; wr = 1; wk = 4; rgs = 1;
+    } else if (RT <= 4) {
+        tpw = 2; wr = 2; wk = 2; rgs = 1;
+    } else {
+        wr = 4; wk = 1;
+        rgs = (RT + 19) / 20;
+        const int per_wg = (RT + rgs - 1) / rgs;
+        tpw = (per_wg + 3) / 4;
+        if (tpw < 2) tpw = 2;
+    }
+    const Variant *v = find_variant(d->qkv_dtype, d->head_dim, tpw, wr, wk);
+    if (!v) return OWL_ERR_UNSUPPORTED;
+
+    const int64_t T = (int64_t)d->max_ctx_len + d->n_draft;
+    int64_t C;
+    if (d->split_tokens > 0) {
+        C = align_up((size_t)d->split_tokens, kSplitQuantum);
+    } else {
+        // Enough workgroups to occupy every compute unit (several rounds when
+        // many independent KV streams exist, which evens out ragged batches),
+        // but splits long enough that the partials they write stay a small
+        // fraction of the K/V bytes they read (ratio ~ 2R / C).
+        const int64_t streams = (int64_t)d->batch * d->n_kv_heads * rgs;
+        const int occ = tpw <= 2 ? 2 : 1;
+        const int rounds = streams >= 64 ? 4 : 1;
+        const int64_t want = (int64_t)device_cus() * occ * rounds;
+        int64_t S = (want + streams - 1) / streams;
+        if (S < 1) S = 1;
+        C = align_up((size_t)((T + S - 1) / S), kSplitQuantum);
+        int64_t cmin = align_up((size_t)(8 * R), kSplitQuantum);
+        if (cmin < 256) cmin = 256;
+        if (C < cmin) C = cmin;
+    }
+    if (C > kMaxSplitTokens) C = kMaxSplitTokens;
+    if (C < kSplitQuantum) C = kSplitQuantum;
+    const int64_t max_splits = (T + C - 1) / C;
+
+    const size_t slots = (size_t)d->batch * d->n_kv_heads * (size_t)max_splits * RT;
+    fp->part_o_bytes = align_up(slots * (size_t)d->head_dim * kRowTile * sizeof(float), 256);
+    fp->part_ml_bytes = align_up(slots * 32 * sizeof(float), 256);
+    fp->variant = v;
+    owl_plan &pl = fp->pub;
+    pl.split_tokens = (int32_t)C;
+    pl.max_splits = (int32_t)max_splits;
+    pl.rows_per_kv = R;
+    pl.row_tiles = RT;
+    pl.row_groups = rgs;
+    pl.tiles_per_wave = tpw;
+    pl.kernel_variant = variant_index(v);
+    pl.n_workgroups = (int32_t)(max_splits * d->n_kv_heads * rgs * d->batch);
+    pl.workspace_bytes = fp->part_o_bytes + fp->part_ml_bytes;
+    return OWL_OK;
+}
+
+// Kernels that need more than the default dynamic LDS must say so once per
+// device before their first launch.
+owl_status ensure_lds_attr(const Variant *v)
+{
+    static std::mutex mu;
+    static bool done[16][64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return OWL_ERR_HIP;
+    const int vi = variant_index(v);
+    if (dev < 0 || dev >= 16 || vi < 0 || vi >= 64) return OWL_ERR_HIP;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!done[dev][vi]) {
+        if (hipFuncSetAttribute(v->func, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)v->lds_bytes) != hipSuccess)
+            return OWL_ERR_HIP;
+        done[dev][vi] = true;
+    }
+    return OWL_OK;
+}
+
+bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
+
+}  // namespace
+
+extern "C" {
+
+owl_status owl_verify_attn_plan(const owl_verify_desc *desc, owl_plan *plan)
+{
+    if (!plan) return OWL_ERR_INVALID_ARG;
+    FullPlan fp;
+    owl_status st = make_plan(desc, &fp);
+    if (st != OWL_OK) return st;
+    *plan = fp.pub;
+    return OWL_OK;
+}
+
+owl_status owl_verify_attn_workspace_size(const owl_verify_desc *desc, size_t *bytes)
+{
+    if (!bytes) return OWL_ERR_INVALID_ARG;
+    FullPlan fp;
+    owl_status st = make_plan(desc, &fp);
+    if (st != OWL_OK) return st;
+    *bytes = fp.pub.workspace_bytes;
+    return OWL_OK;
+}
+
+owl_status owl_verify_attn(const owl_verify_desc *desc, const void *q, const void *k_cache,
+                           const void *v_cache, const int32_t *page_table,
+                           const int32_t *ctx_lens, const int32_t *tree_parent, float *out,
+                           void *workspace, size_t workspace_bytes, uint32_t *dev_status,
+                           void *stream)
+{
+    FullPlan fp;
+    owl_status st = make_plan(desc, &fp);
+    if (st != OWL_OK) return st;
+    if (!q || !k_cache || !v_cache || !ctx_lens || !tree_parent || !out) return OWL_ERR_INVALID_ARG;
+    if (misaligned(q, 16) || misaligned(k_cache, 16) || misaligned(v_cache, 16) || misaligned(out, 16))
+        return OWL_ERR_INVALID_ARG;
+    if (page_table &&
+        (int64_t)desc->max_pages_per_seq * kPage < (int64_t)desc->max_ctx_len + desc->n_draft)
+        return OWL_ERR_INVALID_ARG;
+    if (!workspace || workspace_bytes < fp.pub.workspace_bytes) return OWL_ERR_WORKSPACE;
+    if (misaligned(workspace, 256)) return OWL_ERR_INVALID_ARG;
+
+    st = ensure_lds_attr(fp.variant);
+    if (st != OWL_OK) return st;
+
+    KParams p;
+    memset(&p, 0, sizeof p);
+    p.q = q; p.k = k_cache; p.v = v_cache;
+    p.page_table = page_table; p.ctx_lens = ctx_lens; p.parent = tree_parent;
+    p.part_o = static_cast<float *>(workspace);
+    p.part_ml = reinterpret_cast<float *>(static_cast<char *>(workspace) + fp.part_o_bytes);
+    p.out = out;
+    p.dev_status = dev_status;
+    p.B = desc->batch; p.N = desc->n_draft; p.Hq = desc->n_q_heads; p.Hkv = desc->n_kv_heads;
+    p.G = p.Hq / p.Hkv; p.R = fp.pub.rows_per_kv;
+    p.max_pages = desc->max_pages_per_seq; p.max_ctx_len = desc->max_ctx_len;
+    p.C = fp.pub.split_tokens; p.max_splits = fp.pub.max_splits;
+    p.RT = fp.pub.row_tiles; p.row_groups = fp.pub.row_groups;
+    p.stride_page = desc->kv_stride_page; p.stride_head = desc->kv_stride_head;
+    p.stride_token = desc->kv_stride_token; p.n_pool_pages = desc->n_pool_pages;
+    p.c_log2 = desc->scale * 1.4426950408889634f;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    dim3 grid(p.max_splits, p.Hkv * p.row_groups, p.B);
+    fp.variant->launch(p, grid, s);
+    if (hipGetLastError() != hipSuccess) return OWL_ERR_HIP;
+    if (launch_combine(p, desc->head_dim, s) != hipSuccess) return OWL_ERR_HIP;
+    return OWL_OK;
+}
+
+owl_status owl_build_tree_mask(const int32_t *tree_parent, int32_t batch, int32_t n_draft,
+                               uint64_t *anc_mask, int32_t *depth, uint32_t *dev_status,
+                               void *stream)
+{
+    if (!tree_parent || !anc_mask || batch < 1 || n_draft < 1) return OWL_ERR_INVALID_ARG;
+    if (n_draft > 64) return OWL_ERR_TOO_MANY_DRAFT;
+    if (launch_tree_mask(tree_parent, batch, n_draft, anc_mask, depth, dev_status,
+                         static_cast<hipStream_t>(stream)) != hipSuccess)
+        return OWL_ERR_HIP;
+    return OWL_OK;
+}
+
+owl_status owl_build_tree_mask_host(const int32_t *parent, int32_t n_draft, uint64_t *anc,
+                                    int32_t *depth)
+{
+    if (!parent || !anc || n_draft < 1) return OWL_ERR_INVALID_ARG;
+    if (n_draft > 64) return OWL_ERR_TOO_MANY_DRAFT;
+    for (int i = 0; i < n_draft; ++i)
+        if (parent[i] < -1 || parent[i] >= i) return OWL_ERR_BAD_TREE;
+    // parents come first, so one forward sweep suffices
+    for (int i = 0; i < n_draft; ++i) {
+        const int pi = parent[i];
+        anc[i] = ((uint64_t)1 << i) | (pi >= 0 ? anc[pi] : 0);
+        if (depth) depth[i] = 1 + (pi >= 0 ? depth[pi] : 0);
+    }
+    return OWL_OK;
+}
+
+owl_status owl_gather_kv(const owl_verify_desc *desc, const void *cache, const int32_t *page_table,
+                         int32_t seq, int64_t first_pos, int64_t n_tokens, void *dst,
+                         uint32_t *dev_status, void *stream)
+{
+    owl_status st = check_desc(desc);
+    if (st != OWL_OK) return st;
+    if (!cache || !dst || seq < 0 || seq >= desc->batch || first_pos < 0 || n_tokens < 0)
+        return OWL_ERR_INVALID_ARG;
+    if (misaligned(cache, 16) || misaligned(dst, 16)) return OWL_ERR_INVALID_ARG;
+    if (launch_gather(*desc, cache, page_table, seq, first_pos, n_tokens, dst, dev_status,
+                      static_cast<hipStream_t>(stream)) != hipSuccess)
+        return OWL_ERR_HIP;
+    return OWL_OK;
+}
+
+const char *owl_status_str(owl_status s)
+{
+    switch (s) {
+    case OWL_OK: return "ok";
+    case OWL_ERR_INVALID_ARG: return "invalid argument";
+    case OWL_ERR_BAD_TREE: return "tree_parent is not a forest in parent-first order";
+    case OWL_ERR_TOO_MANY_DRAFT: return "n_draft exceeds 64";
+    case OWL_ERR_UNSUPPORTED: return "unsupported head_dim, page_size, dtype or shape";
+    case OWL_ERR_WORKSPACE: return "workspace missing or too small";
+    case OWL_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+const char *owl_version(void) { return "0.1"; }
+
+}  // extern "C"

@@ -1,0 +1,137 @@
+// Log-sum-exp combine of the split partials, the tree-mask builder and the
+// page-gather test hook.
+#include "owl_device.h"
+
+namespace owl {
+
+// ---------------------------------------------------------------------------
+// Combine.  One workgroup per (sequence, KV head, 16-row tile).  A partial of
+// split s is the triple (m_s, l_s, O_s) with O_s = sum_k 2^(x_k - m_s) v_k and
+// l_s = sum_k 2^(x_k - m_s) over the split's visible keys (x = score*log2 e;
+// m_s is the reference the split happened to use, not necessarily its max).
+// With M = max_s m_s:   out = sum_s 2^(m_s-M) O_s / sum_s 2^(m_s-M) l_s.
+// Partials are stored as raw accumulator fragments: float4 index
+// [slot][r][u][lane] holds channels 4*NT*quad + NT*r + 4*u .. +3 of row lane%16.
+// Wave r of the workgroup reduces register row r.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(256) combine_kernel(const KParams p)
+{
+    constexpr int NT = D / 16, NU = NT / 4;
+    const int tg = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int lane = threadIdx.x & 63, r = threadIdx.x >> 6;
+    const int j = lane & 15, qd = lane >> 4;
+
+    const int L = load_ctx_len(p.ctx_lens, b, p.max_ctx_len, nullptr);
+    const int ns = (L + p.N + p.C - 1) / p.C;
+    const size_t slot0 = (((size_t)b * p.Hkv + g) * p.max_splits) * p.RT + tg;
+
+    float M = -INFINITY;
+    for (int s = 0; s < ns; ++s) M = fmaxf(M, p.part_ml[(slot0 + (size_t)s * p.RT) * 32 + j]);
+
+    float4 acc[NU];
+#pragma unroll
+    for (int u = 0; u < NU; ++u) acc[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    float lsum = 0.f;
+    for (int s = 0; s < ns; ++s) {
+        const size_t slot = slot0 + (size_t)s * p.RT;
+        const float w = __builtin_amdgcn_exp2f(p.part_ml[slot * 32 + j] - M);
+        lsum += w * p.part_ml[slot * 32 + 16 + j];
+        const float4 *po = reinterpret_cast<const float4 *>(p.part_o) + slot * (size_t)(NT * 64) + lane;
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const float4 x = po[(r * NU + u) * 64];
+            acc[u].x += w * x.x; acc[u].y += w * x.y; acc[u].z += w * x.z; acc[u].w += w * x.w;
+        }
+    }
+    const int row = tg * kRowTile + j;
+    if (row >= p.R) return;
+    const int i = row / p.G, hh = row % p.G;
+    const float inv = 1.0f / lsum;
+    float *o = p.out + (((int64_t)b * p.N + i) * p.Hq + g * p.G + hh) * D + 4 * NT * qd + NT * r;
+#pragma unroll
+    for (int u = 0; u < NU; ++u)
+        *reinterpret_cast<float4 *>(o + 4 * u) =
+            make_float4(acc[u].x * inv, acc[u].y * inv, acc[u].z * inv, acc[u].w * inv);
+}
+
+hipError_t launch_combine(const KParams &p, int D, hipStream_t s)
+{
+    dim3 grid(p.RT, p.Hkv, p.B);
+    if (D == 128)
+        hipLaunchKernelGGL(combine_kernel<128>, grid, dim3(256), 0, s, p);
+    else
+        hipLaunchKernelGGL(combine_kernel<64>, grid, dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Tree mask: one wavefront per sequence, lane i walks node i's root path.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(64) tree_mask_kernel(const int32_t *parent, int N, uint64_t *anc,
+                                                       int32_t *depth, uint32_t *status)
+{
+    __shared__ int32_t s_parent[64];
+    const int b = blockIdx.x, i = threadIdx.x;
+    if (i < N) s_parent[i] = parent[(int64_t)b * N + i];
+    __syncthreads();
+    if (i < N) {
+        int d;
+        anc[(int64_t)b * N + i] = ancestor_set(s_parent, i, &d, status);
+        if (depth) depth[(int64_t)b * N + i] = d;
+    }
+}
+
+hipError_t launch_tree_mask(const int32_t *parent, int B, int N, uint64_t *anc, int32_t *depth,
+                            uint32_t *status, hipStream_t s)
+{
+    hipLaunchKernelGGL(tree_mask_kernel, dim3(B), dim3(64), 0, s, parent, N, anc, depth, status);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Gather: dst[t][g][:] = cache row of logical position first + t, 16 bytes per
+// thread.  Same page walk as the split-KV pass.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) gather_kernel(const unsigned char *cache,
+                                                     const int32_t *page_table, int seq,
+                                                     int max_pages, int64_t n_pool_pages, int Hkv,
+                                                     int row_bytes, int es, int64_t stride_page,
+                                                     int64_t stride_head, int64_t stride_token,
+                                                     int64_t first, int64_t n, unsigned char *dst,
+                                                     uint32_t *status)
+{
+    const int ppr = row_bytes / 16;
+    const int64_t total = n * Hkv * ppr;
+    for (int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x; id < total;
+         id += (int64_t)gridDim.x * 256) {
+        const int piece = (int)(id % ppr);
+        const int g = (int)((id / ppr) % Hkv);
+        const int64_t t = id / ((int64_t)ppr * Hkv);
+        const int64_t pos = first + t;
+        const int64_t pg = load_page(page_table, seq, max_pages, n_pool_pages, (int)(pos / kPage), status);
+        const int64_t off = (pg * stride_page + g * stride_head + (pos % kPage) * stride_token) * es;
+        *reinterpret_cast<uint4 *>(dst + (t * Hkv + g) * row_bytes + piece * 16) =
+            *reinterpret_cast<const uint4 *>(cache + off + piece * 16);
+    }
+}
+
+hipError_t launch_gather(const owl_verify_desc &d, const void *cache, const int32_t *page_table,
+                         int seq, int64_t first, int64_t n, void *dst, uint32_t *status,
+                         hipStream_t s)
+{
+    if (n == 0) return hipSuccess;
+    const int es = d.qkv_dtype == OWL_F32 ? 4 : 2;
+    const int row_bytes = d.head_dim * es;
+    const int64_t total = n * d.n_kv_heads * (row_bytes / 16);
+    int blocks = (int)((total + 255) / 256);
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(gather_kernel, dim3(blocks), dim3(256), 0, s,
+                       static_cast<const unsigned char *>(cache), page_table, seq,
+                       d.max_pages_per_seq, d.n_pool_pages, d.n_kv_heads, row_bytes, es,
+                       d.kv_stride_page, d.kv_stride_head, d.kv_stride_token, first, n,
+                       static_cast<unsigned char *>(dst), status);
+    return hipGetLastError();
+}
+
+}  // namespace owl

@@ -1,0 +1,54 @@
+// Internal declarations shared by the host layer and the kernel translation
+// units of the verify-attention library.  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "owl.h"
+
+namespace owl {
+
+constexpr int kPage = 16;                 // tokens per cache page
+constexpr int kRowTile = 16;              // query rows per MFMA tile
+constexpr int kMaxSplitTokens = 16384;    // bounds the per-workgroup page list in LDS
+constexpr int kMaxPagesPerSplit = kMaxSplitTokens / kPage;
+constexpr int kSplitQuantum = 128;        // split_tokens is a multiple of every stage size
+
+// Everything a kernel needs, passed by value.
+struct KParams {
+    const void *q, *k, *v;
+    const int32_t *page_table, *ctx_lens, *parent;
+    float *part_o;        // split partials: accumulator fragments
+    float *part_ml;       // split partials: running reference m and row sum l
+    float *out;
+    uint32_t *dev_status;
+    int32_t B, N, Hq, Hkv, G, R;
+    int32_t max_pages, max_ctx_len;
+    int32_t C;            // tokens per split
+    int32_t max_splits;
+    int32_t RT;           // row tiles covering R
+    int32_t row_groups;
+    int64_t stride_page, stride_head, stride_token, n_pool_pages;
+    float c_log2;         // scale * log2(e): scores live in the exp2 domain
+};
+
+// One instantiated split-KV kernel.
+struct Variant {
+    int dtype, D, tpw, wr, wk;
+    size_t lds_bytes;
+    void (*launch)(const KParams &, dim3 grid, hipStream_t);
+    const void *func;     // for hipFuncSetAttribute
+};
+
+const Variant *find_variant(int dtype, int D, int tpw, int wr, int wk);
+int variant_index(const Variant *v);
+
+hipError_t launch_combine(const KParams &p, int D, hipStream_t s);
+hipError_t launch_tree_mask(const int32_t *parent, int B, int N, uint64_t *anc, int32_t *depth,
+                            uint32_t *status, hipStream_t s);
+hipError_t launch_gather(const owl_verify_desc &d, const void *cache, const int32_t *page_table,
+                         int seq, int64_t first, int64_t n, void *dst, uint32_t *status,
+                         hipStream_t s);
+
+}  // namespace owl

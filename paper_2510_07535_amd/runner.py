@@ -1,0 +1,62 @@
+"""Device residency for one verify step: uploads a ``workloads.Case`` once,
+owns the output / workspace / status buffers, and calls the C ABI.  Only
+memory management and argument marshalling happen here."""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+from . import workloads as W
+
+
+def _to_dev(a: np.ndarray, device) -> torch.Tensor:
+    """Upload without reinterpreting bits (uint16 carries bf16/f16 patterns)."""
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(device)
+    return torch.from_numpy(a).to(device)
+
+
+class VerifyStep:
+    def __init__(self, case: W.Case, device: str = "cuda:0", split_tokens: int = 0,
+                 max_ctx_len: Optional[int] = None):
+        self.case = case
+        self.device = torch.device(device)
+        self.q = _to_dev(case.q, self.device)
+        self.k = _to_dev(case.k_pool, self.device)
+        self.v = _to_dev(case.v_pool, self.device)
+        self.page_table = None if case.page_table is None else _to_dev(case.page_table, self.device)
+        self.ctx_lens = _to_dev(case.ctx_lens, self.device)
+        self.tree_parent = _to_dev(np.ascontiguousarray(case.tree_parent), self.device)
+        self.out = torch.empty((case.B, case.N, case.Hq, case.D), dtype=torch.float32, device=self.device)
+        self.status = torch.zeros(1, dtype=torch.int32, device=self.device)
+        self.desc = B.make_desc(
+            batch=case.B, n_draft=case.N, n_q_heads=case.Hq, n_kv_heads=case.Hkv, head_dim=case.D,
+            max_pages_per_seq=case.max_pages_per_seq,
+            max_ctx_len=case.max_ctx_len if max_ctx_len is None else max_ctx_len,
+            qkv_dtype=case.dtype, scale=case.scale, kv_stride_page=case.stride_page,
+            kv_stride_head=case.stride_head, kv_stride_token=case.stride_token,
+            n_pool_pages=case.n_pool_pages, split_tokens=split_tokens)
+        self.plan = B.owl_verify_attn_plan(self.desc)
+        self.workspace = torch.empty(max(self.plan.workspace_bytes, 256), dtype=torch.uint8,
+                                     device=self.device)
+
+    def run(self, k=None, v=None, page_table=None, stream: Optional[int] = None) -> torch.Tensor:
+        """One verify step.  ``k``/``v``/``page_table`` let a caller rotate
+        through several resident copies of the cache."""
+        B.owl_verify_attn(self.desc, self.q, self.k if k is None else k,
+                          self.v if v is None else v,
+                          self.page_table if page_table is None else page_table,
+                          self.ctx_lens, self.tree_parent, self.out, self.workspace, self.status,
+                          stream=stream)
+        return self.out
+
+    def result(self) -> np.ndarray:
+        torch.cuda.synchronize(self.device)
+        return self.out.cpu().numpy()
+
+    def dev_status(self) -> int:
+        torch.cuda.synchronize(self.device)
+        return int(self.status.item())

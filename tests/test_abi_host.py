@@ -1,0 +1,116 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol
+the header declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2510_07535_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _good(**over):
+    kw = dict(batch=1, n_draft=6, n_q_heads=32, n_kv_heads=8, head_dim=128, max_pages_per_seq=2049,
+              max_ctx_len=32768, qkv_dtype=B.OWL_BF16, scale=0.0883883, kv_stride_page=8 * 16 * 128,
+              kv_stride_head=16 * 128, kv_stride_token=128, n_pool_pages=2049)
+    kw.update(over)
+    return B.make_desc(**kw)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "owl.h")).read()
+    declared = set(re.findall(r"\b(owl_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
+    lib = B.lib()
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert lib.owl_version().decode().count(".") == 1
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(B.VerifyDesc) == 12 * 4 + 4 * 8
+    assert B.VerifyDesc.kv_stride_page.offset == 48
+    assert ctypes.sizeof(B.Plan) == 8 * 4 + 8
+
+
+def test_plan_matches_shapes():
+    p = B.owl_verify_attn_plan(_good())
+    assert p.rows_per_kv == 24 and p.row_tiles == 2 and p.row_groups == 1
+    assert p.split_tokens % 128 == 0 and p.split_tokens * p.max_splits >= 32768 + 6
+    assert p.workspace_bytes == B.owl_verify_attn_workspace_size(_good())
+    p = B.owl_verify_attn_plan(_good(n_draft=40, n_q_heads=64, max_ctx_len=131072, max_pages_per_seq=8200))
+    assert p.rows_per_kv == 320 and p.row_tiles == 20 and p.tiles_per_wave == 5
+    p = B.owl_verify_attn_plan(_good(split_tokens=1000))
+    assert p.split_tokens == 1024
+    p = B.owl_verify_attn_plan(_good(n_draft=64, n_q_heads=64))        # 512 rows
+    assert p.row_tiles == 32 and p.row_groups == 2
+
+
+@pytest.mark.parametrize("over,code", [
+    (dict(batch=0), B.OWL_ERR_INVALID_ARG),
+    (dict(n_draft=0), B.OWL_ERR_INVALID_ARG),
+    (dict(n_draft=65), B.OWL_ERR_TOO_MANY_DRAFT),
+    (dict(n_q_heads=30), B.OWL_ERR_INVALID_ARG),
+    (dict(head_dim=96), B.OWL_ERR_UNSUPPORTED),
+    (dict(page_size=32), B.OWL_ERR_UNSUPPORTED),
+    (dict(qkv_dtype=7), B.OWL_ERR_UNSUPPORTED),
+    (dict(scale=0.0), B.OWL_ERR_INVALID_ARG),
+    (dict(scale=float("nan")), B.OWL_ERR_INVALID_ARG),
+    (dict(max_ctx_len=-1), B.OWL_ERR_INVALID_ARG),
+    (dict(kv_stride_token=100), B.OWL_ERR_INVALID_ARG),
+    (dict(kv_stride_head=2052), B.OWL_ERR_INVALID_ARG),
+    (dict(n_pool_pages=0), B.OWL_ERR_INVALID_ARG),
+    (dict(split_tokens=-5), B.OWL_ERR_INVALID_ARG),
+])
+def test_bad_descriptors_are_rejected(over, code):
+    with pytest.raises(B.OwlError) as e:
+        B.owl_verify_attn_plan(_good(**over))
+    assert e.value.code == code
+
+
+def test_verify_attn_rejects_before_launch():
+    """Null / misaligned pointers and a short workspace come back as errors
+    without touching a device (fake non-null addresses are never dereferenced
+    on these paths)."""
+    lib = B.lib()
+    d = _good()
+    need = B.owl_verify_attn_workspace_size(d)
+    A = 0x10000
+    args = [A, A, A, A, A, A, A, A, need, None, None]      # q k v pt ctx parent out ws bytes status stream
+    def call(a):
+        return lib.owl_verify_attn(ctypes.byref(d), *a)
+    for null_at in (0, 1, 2, 4, 5, 6):
+        a = list(args); a[null_at] = None
+        assert call(a) == B.OWL_ERR_INVALID_ARG
+    a = list(args); a[7] = None
+    assert call(a) == B.OWL_ERR_WORKSPACE
+    a = list(args); a[8] = need - 1
+    assert call(a) == B.OWL_ERR_WORKSPACE
+    a = list(args); a[0] = A + 2
+    assert call(a) == B.OWL_ERR_INVALID_ARG
+    a = list(args); a[7] = A + 16
+    assert call(a) == B.OWL_ERR_INVALID_ARG
+    short = _good(max_pages_per_seq=100)                    # table cannot cover max_ctx_len + N
+    assert lib.owl_verify_attn(ctypes.byref(short), *args) == B.OWL_ERR_INVALID_ARG
+    assert lib.owl_verify_attn(None, *args) == B.OWL_ERR_INVALID_ARG
+
+
+def test_mask_host_twin():
+    anc, dep = B.owl_build_tree_mask_host(np.array([-1, 0, 0, 0, 1, 2], np.int32))
+    assert list(anc) == [0b1, 0b11, 0b101, 0b1001, 0b10011, 0b100101]
+    assert list(dep) == [1, 2, 2, 2, 3, 3]
+    for bad in ([0], [-1, 1], [-3], [-1, 0, 3]):
+        with pytest.raises(B.OwlError) as e:
+            B.owl_build_tree_mask_host(np.array(bad, np.int32))
+        assert e.value.code == B.OWL_ERR_BAD_TREE
+    with pytest.raises(B.OwlError) as e:
+        B.owl_build_tree_mask_host(np.arange(-1, 64, dtype=np.int32))
+    assert e.value.code == B.OWL_ERR_TOO_MANY_DRAFT
+    lib = B.lib()
+    assert lib.owl_build_tree_mask(None, 1, 4, 0x1000, None, None, None) == B.OWL_ERR_INVALID_ARG
+    assert lib.owl_build_tree_mask(0x1000, 1, 65, 0x1000, None, None, None) == B.OWL_ERR_TOO_MANY_DRAFT
+    assert lib.owl_gather_kv(ctypes.byref(_good()), None, None, 0, 0, 1, 0x1000, None, None) == B.OWL_ERR_INVALID_ARG
+    assert "workspace" in B.status_str(B.OWL_ERR_WORKSPACE)

@@ -1,0 +1,251 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Everything here needs an MI355X (-m gpu)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2510_07535_amd import binding as B
+from paper_2510_07535_amd import workloads as W
+from paper_2510_07535_amd.runner import VerifyStep, _to_dev
+from util import assert_close, sample_rows
+
+pytestmark = pytest.mark.gpu
+
+
+def _rng(k):
+    return np.random.Generator(np.random.Philox(key=k))
+
+
+def _run(case, **kw):
+    step = VerifyStep(case, **kw)
+    step.run()
+    out = step.result()
+    assert step.dev_status() == 0
+    return out, step
+
+
+# ---------------------------------------------------------------------------
+# small and ragged shapes, full element-by-element comparison
+# ---------------------------------------------------------------------------
+def _small_cases():
+    r = _rng(1234)
+    mk = W.make_case
+    cs = [
+        # several 64-key stages, ragged tail, chain (row tiles: 2)
+        mk("bf16_chain6_L1000", 101, dtype=W.DT_BF16, Hq=32, Hkv=8, D=128, ctx_lens=[1000], trees=[W.chain_tree(6)]),
+        # one row tile, n_draft = 1 (plain decode)
+        mk("bf16_decode_L777", 102, dtype=W.DT_BF16, Hq=8, Hkv=2, D=128, ctx_lens=[777], trees=[W.chain_tree(1)]),
+        # empty prefix: only the drafts are visible
+        mk("bf16_L0_tree20", 103, dtype=W.DT_BF16, Hq=8, Hkv=2, D=128, ctx_lens=[0], trees=[W.random_tree(20, 5, r)]),
+        # prefix shorter than a page / exactly a page; drafts straddle pages
+        mk("bf16_L15_L16_L17", 104, dtype=W.DT_BF16, Hq=4, Hkv=2, D=128, ctx_lens=[15, 16, 17],
+           trees=[W.random_tree(9, 4, r) for _ in range(3)]),
+        # 3..4 row tiles -> 2x2 wave layout
+        mk("bf16_tree14_G4", 105, dtype=W.DT_BF16, Hq=8, Hkv=2, D=128, ctx_lens=[2500], trees=[W.random_tree(14, 4, r)]),
+        # 7 row tiles (the batched configuration's tile count), ragged batch
+        mk("bf16_tree26_batch3", 106, dtype=W.DT_BF16, Hq=32, Hkv=8, D=128, ctx_lens=[3000, 129, 1999],
+           trees=[W.random_tree(26, 5, r) for _ in range(3)]),
+        # 15 row tiles (60-node tree, G=4)
+        mk("bf16_tree60", 107, dtype=W.DT_BF16, Hq=8, Hkv=2, D=128, ctx_lens=[1500], trees=[W.random_tree(60, 6, r)]),
+        # 20 row tiles (40 nodes, G=8) with outlier keys
+        mk("bf16_hybrid40_G8", 108, dtype=W.DT_BF16, Hq=16, Hkv=2, D=128, ctx_lens=[2100],
+           trees=[W.hybrid_tree(32, 8, r)], outlier_frac=0.05),
+        # maximum draft count, G=8 -> 32 row tiles -> two row groups
+        mk("bf16_chain64_G8", 109, dtype=W.DT_BF16, Hq=8, Hkv=1, D=128, ctx_lens=[700], trees=[W.chain_tree(64)]),
+        # head_dim 64, token-major cache layout, G=1
+        mk("bf16_D64_tokmajor", 110, dtype=W.DT_BF16, Hq=4, Hkv=4, D=64, ctx_lens=[900, 64],
+           trees=[W.random_tree(12, 4, r) for _ in range(2)], head_major=False),
+        mk("bf16_D64_tree40", 111, dtype=W.DT_BF16, Hq=16, Hkv=4, D=64, ctx_lens=[1300], trees=[W.random_tree(40, 8, r)]),
+        # identity paging (page_table NULL)
+        mk("bf16_identity_pages", 112, dtype=W.DT_BF16, Hq=8, Hkv=2, D=128, ctx_lens=[555], trees=[W.random_tree(7, 3, r)],
+           paged=False),
+        # forest: several roots
+        mk("bf16_forest", 113, dtype=W.DT_BF16, Hq=4, Hkv=1, D=128, ctx_lens=[300],
+           trees=[np.array([-1, -1, 0, 1, 1, -1, 5, 2], np.int32)]),
+        # fp16 storage (the paper's inference type)
+        mk("f16_tree30", 114, dtype=W.DT_F16, Hq=16, Hkv=4, D=128, ctx_lens=[1100], trees=[W.spec_tree(W.random_tree(15, 4, r))]),
+        # fp32 storage, both head dims
+        mk("f32_D64_tree10", 115, dtype=W.DT_F32, Hq=8, Hkv=2, D=64, ctx_lens=[700, 33], trees=[W.random_tree(10, 4, r) for _ in range(2)]),
+        mk("f32_D128_chain5", 116, dtype=W.DT_F32, Hq=4, Hkv=2, D=128, ctx_lens=[390], trees=[W.chain_tree(5)]),
+    ]
+    return cs
+
+
+@pytest.mark.parametrize("case", _small_cases(), ids=lambda c: c.name)
+def test_small_shapes_match_oracle(oracle_mod, case):
+    want = oracle_mod.verify_attn_case(case)
+    for split in (0, 128, 512):
+        got, step = _run(case, split_tokens=split)
+        assert_close(got, want, case.dtype, f"{case.name} split={split} plan={step.plan.as_dict()}")
+
+
+# ---------------------------------------------------------------------------
+# the five named configurations
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("idx", range(5), ids=W.CONFIG_NAMES)
+def test_configs_reduced_context_full_compare(oracle_mod, idx):
+    """Same head shapes, trees and paging as the named configuration with the
+    context cut to 1/16 (config 0 runs at its full 512 tokens), every output
+    element compared."""
+    case = W.make_config(idx, ctx_scale=1.0 if idx == 0 else 1.0 / 16)
+    want = oracle_mod.verify_attn_case(case)
+    got, step = _run(case)
+    assert_close(got, want, case.dtype, f"{case.name} plan={step.plan.as_dict()}")
+
+
+@pytest.mark.parametrize("idx", range(5), ids=W.CONFIG_NAMES)
+def test_configs_full_size_sampled_rows(oracle_mod, idx):
+    """Full context lengths, in the launch configuration the benchmark times
+    (library-chosen splits); the oracle computes a sample of output rows."""
+    case = W.make_config(idx)
+    got, step = _run(case)
+    nrows = 96 if idx < 4 else 64
+    rows = sample_rows(case, nrows, seed=idx, always=[(0, 0, 0), (case.B - 1, case.N - 1, case.Hq - 1)])
+    want = oracle_mod.verify_attn_case(case, rows=rows)
+    sub = np.stack([got[b, i, h] for b, i, h in rows])
+    assert_close(sub, want, case.dtype, f"{case.name} plan={step.plan.as_dict()}")
+    assert np.isfinite(got).all()
+
+
+# ---------------------------------------------------------------------------
+# evaluation-order invariance and exact properties on the GPU
+# ---------------------------------------------------------------------------
+def test_split_count_invariance(oracle_mod):
+    """1 split vs many splits vs the planner's choice: all within tolerance of
+    the oracle and of each other (catches combine races and stale partials)."""
+    case = W.make_case("splitinv", 201, dtype=W.DT_BF16, Hq=32, Hkv=8, D=128, ctx_lens=[6000, 4097],
+                       trees=[W.random_tree(26, 5, _rng(5)) for _ in range(2)])
+    want = oracle_mod.verify_attn_case(case)
+    outs = []
+    for split in (16384, 4096, 1024, 128, 0):
+        got, _ = _run(case, split_tokens=split)
+        assert_close(got, want, case.dtype, f"split={split}")
+        outs.append(got)
+    for o in outs[1:]:
+        assert np.abs(o - outs[0]).max() < 5e-3
+
+
+def test_non_ancestor_perturbation_is_invisible():
+    """Overwriting K/V of draft j must leave every row whose path does not
+    contain j bit-identical."""
+    tree = W.random_tree(20, 5, _rng(7))
+    base_case = W.make_case("perturb", 202, dtype=W.DT_BF16, Hq=8, Hkv=2, D=128, ctx_lens=[1000], trees=[tree])
+    base, _ = _run(base_case)
+    on_path = np.zeros((20, 20), bool)
+    for i in range(20):
+        j = i
+        while j != -1:
+            on_path[i, j] = True
+            j = int(tree[j])
+    for j in (0, 3, 11, 19):
+        c2 = W.make_case("perturb", 202, dtype=W.DT_BF16, Hq=8, Hkv=2, D=128, ctx_lens=[1000], trees=[tree])
+        pos = 1000 + j
+        page = int(c2.page_table[0, pos // 16])
+        c2.k_pool[page, :, pos % 16, :] = W.store(np.full((2, 128), 2.0, np.float32), W.DT_BF16)
+        c2.v_pool[page, :, pos % 16, :] = W.store(np.full((2, 128), -9.0, np.float32), W.DT_BF16)
+        got, _ = _run(c2)
+        for i in range(20):
+            if on_path[i, j]:
+                assert np.abs(got[0, i] - base[0, i]).max() > 1e-4, (i, j)
+            else:
+                assert np.array_equal(got[0, i], base[0, i]), (i, j)
+
+
+def test_page_permutation_is_invisible():
+    kw = dict(dtype=W.DT_BF16, Hq=8, Hkv=2, D=128, ctx_lens=[3000, 700],
+              trees=[W.random_tree(12, 4, _rng(8)) for _ in range(2)])
+    a, _ = _run(W.make_case("perm", 203, paged=True, **kw))
+    b, _ = _run(W.make_case("perm", 203, paged=False, **kw))
+    c, _ = _run(W.make_case("perm", 203, paged=True, head_major=False, **kw))
+    assert np.array_equal(a, b)
+    assert np.array_equal(a, c)
+
+
+def test_zero_query_integer_values_exact_mean():
+    """q = 0, small-integer V, L + depth a power of two for the chain's last
+    node: every weight is exactly 1, so the mean must be exact in fp32 -- any
+    wrong, missing or doubled cache row shows up as a bit difference."""
+    N, L = 4, 4096 - 4
+    case = W.make_case("exact", 204, dtype=W.DT_BF16, Hq=4, Hkv=2, D=128, ctx_lens=[L], trees=[W.chain_tree(N)])
+    case.q[...] = 0
+    r = _rng(9)
+    T = L + N
+    vals = r.integers(-8, 9, size=(T, 2, 128)).astype(np.float32)
+    for pos in range(T):
+        page = int(case.page_table[0, pos // 16])
+        case.v_pool[page, :, pos % 16, :] = W.store(vals[pos], W.DT_BF16)
+    for split in (0, 128, 1024):
+        got, _ = _run(case, split_tokens=split)
+        want = vals.sum(axis=0, dtype=np.float64) / T            # last node sees all T rows
+        for h in range(4):
+            assert np.array_equal(got[0, N - 1, h].astype(np.float64), want[h // 2]), split
+
+
+# ---------------------------------------------------------------------------
+# mask builder and paging: bit-exact
+# ---------------------------------------------------------------------------
+def test_tree_mask_bit_exact(oracle_mod):
+    r = _rng(10)
+    trees64 = [W.random_tree(64, md, r) for md in (None, 2, 8)] + [W.chain_tree(64), np.full(64, -1, np.int32)]
+    trees6 = [W.spec_tree([-1, 0, 0]), W.chain_tree(6)]
+    for trees in (trees64, trees6, [W.chain_tree(1)]):
+        par = np.stack(trees).astype(np.int32)
+        Bn, N = par.shape
+        dpar = torch.from_numpy(par).cuda()
+        anc = torch.zeros((Bn, N), dtype=torch.int64, device="cuda")
+        dep = torch.zeros((Bn, N), dtype=torch.int32, device="cuda")
+        st = torch.zeros(1, dtype=torch.int32, device="cuda")
+        B.owl_build_tree_mask(dpar, anc, dep, st)
+        torch.cuda.synchronize()
+        assert int(st.item()) == 0
+        for b in range(Bn):
+            want_anc, want_dep = oracle_mod.tree_mask(par[b])
+            assert np.array_equal(anc[b].cpu().numpy().view(np.uint64), want_anc)
+            assert np.array_equal(dep[b].cpu().numpy(), want_dep)
+            h_anc, h_dep = B.owl_build_tree_mask_host(par[b])
+            assert np.array_equal(h_anc, want_anc) and np.array_equal(h_dep, want_dep)
+
+
+def test_gather_bit_exact(oracle_mod):
+    for head_major, dtype in ((True, W.DT_BF16), (False, W.DT_BF16), (True, W.DT_F32)):
+        case = W.make_case("gather", 301, dtype=dtype, Hq=8, Hkv=4, D=128, ctx_lens=[1000, 37, 4000],
+                           trees=[W.chain_tree(5)] * 3, head_major=head_major, spare_pages=7)
+        step = VerifyStep(case)
+        for b in range(case.B):
+            T = int(case.ctx_lens[b]) + case.N
+            for which, cache in (("k", step.k), ("v", step.v)):
+                dst = torch.empty((T, case.Hkv, case.D), dtype=cache.dtype, device="cuda")
+                B.owl_gather_kv(step.desc, cache, step.page_table, b, 0, T, dst, step.status)
+                torch.cuda.synchronize()
+                want = oracle_mod.gather_kv(case, which, b, 0, T)
+                got = dst.cpu().numpy()
+                assert np.array_equal(got.view(want.dtype), want)
+        assert step.dev_status() == 0
+
+
+# ---------------------------------------------------------------------------
+# data errors on the device are flagged, never followed out of bounds
+# ---------------------------------------------------------------------------
+def test_device_side_errors_are_flagged():
+    tree = W.random_tree(10, 4, _rng(11))
+    def fresh():
+        return W.make_case("bad", 401, dtype=W.DT_BF16, Hq=8, Hkv=2, D=128, ctx_lens=[500, 300], trees=[tree, tree])
+    c = fresh()
+    c.tree_parent[1, 4] = 7                      # child before parent
+    s = VerifyStep(c); s.run()
+    assert s.dev_status() & B.OWL_DEV_BAD_PARENT
+    c = fresh()
+    c.page_table[0, 3] = c.n_pool_pages + 5      # page outside the pool
+    s = VerifyStep(c); s.run()
+    assert s.dev_status() & B.OWL_DEV_BAD_PAGE
+    c = fresh()
+    s = VerifyStep(c, max_ctx_len=400)           # ctx_lens[0] = 500 > announced bound
+    s.run()
+    assert s.dev_status() & B.OWL_DEV_BAD_CTX_LEN
+    # the sequence that was fine is still right next to a flagged one
+    par = torch.from_numpy(np.array([[-1, 0, 5, 1]], np.int32)).cuda()
+    anc = torch.zeros((1, 4), dtype=torch.int64, device="cuda")
+    st = torch.zeros(1, dtype=torch.int32, device="cuda")
+    B.owl_build_tree_mask(par, anc, None, st)
+    torch.cuda.synchronize()
+    assert int(st.item()) & B.OWL_DEV_BAD_PARENT
