@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the verify-step attention on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config IDX] [--all]
+
+A step is one call of owl_verify_attn (split-KV pass + log-sum-exp combine)
+over one batch of seeded synthetic input that is already resident in HBM.
+Successive steps walk through several resident copies of the KV cache so that
+more than 2 GB is touched between two uses of the same bytes: a real verify
+step scans 32-80 layers' caches, so the cache is always cold, and the chip's
+256 MB memory-side cache would otherwise serve the smaller shapes.
+
+Prints ONE JSON line.  `value` is algorithmic KV bytes per second
+(sum_b (L_b + N) * Hkv * D * 2 tensors * 2 bytes, divided by the time of the
+whole step); `ms_per_step` is the verify-step time.  `roofline` prices the
+split-KV kernel alone against the 8 TB/s HBM peak; `cpu_baseline` times the CPU
+oracle on a sample of output rows on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MIN_ROTATION_BYTES = 2 << 30
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=3,
+                    help="0-based index into the benchmark configurations (default 3: 128K-context hybrid verify)")
+    ap.add_argument("--all", action="store_true", help="also time the other bf16 configurations (reported under 'others')")
+    ap.add_argument("--split-tokens", type=int, default=0, help="override the library's split size (tuning)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-probe", action="store_true")
+    return ap.parse_args()
+
+
+class Rotating:
+    """A verify step plus enough resident copies of its KV cache to defeat the
+    caches between reuses."""
+
+    def __init__(self, case, split_tokens=0):
+        import torch
+        from paper_2510_07535_amd.runner import VerifyStep
+        self.torch = torch
+        self.step = VerifyStep(case, split_tokens=split_tokens)
+        self.kv_bytes = case.kv_bytes()
+        pool_bytes = 2 * self.step.k.numel() * self.step.k.element_size()
+        n = max(2, -(-MIN_ROTATION_BYTES // max(pool_bytes, 1)))
+        n = min(n, 64)
+        self.pools = [(self.step.k, self.step.v)]
+        for _ in range(n - 1):
+            self.pools.append((self.step.k.clone(), self.step.v.clone()))
+        self.i = 0
+
+    def run(self, phases=3):
+        k, v = self.pools[self.i % len(self.pools)]
+        self.i += 1
+        self.step.run(k=k, v=v, phases=phases)
+
+    def time_steps(self, steps, warmup):
+        torch = self.torch
+        for _ in range(warmup):
+            self.run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.run()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    def time_split_kernel(self, steps):
+        """Average duration of the split-KV kernel alone, from events recorded
+        on the launch stream right around each launch."""
+        torch = self.torch
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        for _ in range(3):
+            self.run()
+        torch.cuda.synchronize()
+        for a, b in ev:
+            a.record()
+            self.run(phases=1)
+            b.record()
+            self.run(phases=2)
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in ev)
+        return sum(ms) / len(ms) * 1e-3, ms[len(ms) // 2] * 1e-3
+
+
+def stream_probe_gbs(nbytes=1 << 30):
+    import torch
+    from paper_2510_07535_amd import binding as B
+    bufs = [torch.empty(nbytes, dtype=torch.uint8, device="cuda").random_(0, 255) for _ in range(3)]
+    sink = torch.zeros(8192, dtype=torch.int32, device="cuda")
+    best = 0.0
+    for nwg in (1024, 2048, 4096):
+        for _ in range(3):
+            B.owl_stream_read_probe(bufs[0], sink, nwg)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        reps = 12
+        for r in range(reps):
+            B.owl_stream_read_probe(bufs[r % 3], sink, nwg)
+        b.record()
+        torch.cuda.synchronize()
+        best = max(best, nbytes * reps / (a.elapsed_time(b) * 1e-3) / 1e9)
+    return best
+
+
+def cpu_baseline(case, budget_rows=None):
+    import numpy as np
+    import oracle
+    oracle.build()
+    total_rows = case.B * case.N * case.Hq
+    # ~10-30 s of host work: the oracle does ~1e10 flop/s on a handful of cores
+    flop_per_row = 4.0 * case.D * float(case.ctx_lens.astype(np.float64).mean() + case.N)
+    n = budget_rows or int(max(16, min(total_rows, 1.5e11 / max(flop_per_row, 1.0))))
+    rng = np.random.Generator(np.random.Philox(key=12345))
+    pick = rng.choice(total_rows, size=min(n, total_rows), replace=False)
+    rows = np.stack([pick // (case.N * case.Hq), (pick // case.Hq) % case.N, pick % case.Hq], axis=1).astype(np.int32)
+    t0 = time.perf_counter()
+    oracle.verify_attn_case(case, rows=rows)
+    dt = time.perf_counter() - t0
+    full = dt * total_rows / len(rows)
+    return {
+        "value": case.kv_bytes() / full / 1e9, "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": f"{len(rows)} of {total_rows} output rows of the same workload in {dt:.1f} s, scaled to all rows "
+                  f"({full:.1f} s per verify step)",
+        "seconds_per_step_est": full,
+    }
+
+
+def bench_config(idx, args, want_detail):
+    from paper_2510_07535_amd import workloads as W
+    case = W.make_config(idx)
+    rot = Rotating(case, split_tokens=args.split_tokens)
+    sec = rot.time_steps(args.steps, args.warmup)
+    res = {
+        "workload": W.CONFIG_NAMES[idx], "config_index": idx,
+        "us_per_step": sec * 1e6, "GBps": rot.kv_bytes / sec / 1e9,
+        "frac_of_hbm_peak": rot.kv_bytes / sec / 1e9 / HBM_PEAK_GBS,
+        "kv_bytes": rot.kv_bytes, "plan": rot.step.plan.as_dict(), "kv_copies_rotated": len(rot.pools),
+    }
+    if want_detail:
+        kavg, kmed = rot.time_split_kernel(min(args.steps, 100))
+        res["split_kernel_avg_s"] = kavg
+        res["split_kernel_median_s"] = kmed
+    assert rot.step.dev_status() == 0
+    return case, rot, res
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build measures ONE GPU (the per-GPU share of the path at its real shape); "
+              f"--gpus {args.gpus} is not supported, run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2510_07535_amd import binding as B
+    from paper_2510_07535_amd import workloads as W
+    B.lib()   # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    case, rot, main_res = bench_config(args.config, args, True)
+    kbytes = main_res["kv_bytes"]
+    achieved = kbytes / main_res["split_kernel_avg_s"] / 1e9
+    line = {
+        "metric": "verify-step attention: achieved HBM GB/s over algorithmic KV bytes (us per step in ms_per_step)",
+        "value": main_res["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_res["us_per_step"] / 1e3, "us_per_step": main_res["us_per_step"],
+        "frac_of_hbm_peak": main_res["frac_of_hbm_peak"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {W.DT_BF16: "bf16", W.DT_F32: "f32", W.DT_F16: "f16"}[case.dtype], "data": "synthetic",
+        "config": {"workload": main_res["workload"], "config_index": args.config, "batch": case.B,
+                   "ctx_lens_max": int(case.ctx_lens.max()), "ctx_tokens_total": int(case.ctx_lens.sum()),
+                   "n_draft": case.N, "n_q_heads": case.Hq, "n_kv_heads": case.Hkv, "head_dim": case.D,
+                   "page_size": 16, "kv_bytes_per_step": kbytes, "kv_copies_rotated": main_res["kv_copies_rotated"],
+                   "plan": main_res["plan"]},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "splitkv_kernel", "kernel_avg_us": main_res["split_kernel_avg_s"] * 1e6,
+                     "kernel_median_us": main_res["split_kernel_median_s"] * 1e6,
+                     "algorithmic_bytes_per_launch": kbytes},
+    }
+    if not args.no_probe:
+        line["roofline"]["stream_read_probe_GBps"] = stream_probe_gbs()
+    if args.all:
+        others = []
+        for idx in (1, 2, 3, 4):
+            if idx == args.config:
+                continue
+            del rot
+            torch.cuda.empty_cache()
+            _, rot, r = bench_config(idx, args, True)
+            others.append(r)
+        line["others"] = others
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(case)
+    else:
+        line["cpu_baseline"] = None
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -142,6 +142,23 @@ owl_status owl_verify_attn(const owl_verify_desc *desc, const void *q, const voi
                            void *stream);
 
 /*
+ * The same step, one phase at a time, for measurement: `phases` is a bit set of
+ * OWL_PHASE_SPLIT (the split-KV pass that scans the cache and leaves partials
+ * in the workspace) and OWL_PHASE_COMBINE (the log-sum-exp merge that turns
+ * the partials into `out`).  OWL_PHASE_ALL is owl_verify_attn.  Running the
+ * combine without a preceding split pass on the same workspace reads garbage
+ * partials (finite or not) but stays in bounds.
+ */
+#define OWL_PHASE_SPLIT 1
+#define OWL_PHASE_COMBINE 2
+#define OWL_PHASE_ALL 3
+owl_status owl_verify_attn_phases(const owl_verify_desc *desc, const void *q, const void *k_cache,
+                                  const void *v_cache, const int32_t *page_table,
+                                  const int32_t *ctx_lens, const int32_t *tree_parent, float *out,
+                                  void *workspace, size_t workspace_bytes, uint32_t *dev_status,
+                                  void *stream, int32_t phases);
+
+/*
  * The attention mask of a drafted tree in packed form (Sec. 3.2.2: "manipulating
  * the position ids and attention mask"; Algorithm 1, Prepare): for every
  * sequence b and node i,
@@ -171,6 +188,16 @@ owl_status owl_build_tree_mask_host(const int32_t *tree_parent_host, int32_t n_d
 owl_status owl_gather_kv(const owl_verify_desc *desc, const void *cache,
                          const int32_t *page_table, int32_t seq, int64_t first_pos,
                          int64_t n_tokens, void *dst, uint32_t *dev_status, void *stream);
+
+/*
+ * Measurement aid: a plain streaming read of `bytes` bytes (multiple of 16,
+ * 16-byte aligned) with 128-bit loads by `n_workgroups` workgroups of 256
+ * threads; every workgroup XOR-folds what it read into sink[workgroup] (uint32,
+ * device).  Its achieved GB/s is the practical ceiling the split-KV pass is
+ * compared with next to the nominal HBM peak.
+ */
+owl_status owl_stream_read_probe(const void *src, size_t bytes, uint32_t *sink,
+                                 int32_t n_workgroups, void *stream);
 
 /* Static string for a status code. */
 const char *owl_status_str(owl_status s);

@@ -7,6 +7,7 @@ verify step's buffers resident on the GPU for tests and benchmarks, and
 """
 from . import binding  # noqa: F401
 from .binding import (  # noqa: F401
-    OwlError, owl_build_tree_mask, owl_build_tree_mask_host, owl_gather_kv, owl_verify_attn,
+    OwlError, owl_build_tree_mask, owl_build_tree_mask_host, owl_gather_kv, owl_stream_read_probe,
+    owl_verify_attn, owl_verify_attn_phases,
     owl_verify_attn_plan, owl_verify_attn_workspace_size,
 )

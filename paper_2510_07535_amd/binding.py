@@ -21,6 +21,7 @@ OWL_DEV_BAD_PARENT, OWL_DEV_BAD_PAGE, OWL_DEV_BAD_CTX_LEN = 1, 2, 4
 
 EXPORTS = (
     "owl_verify_attn_plan", "owl_verify_attn_workspace_size", "owl_verify_attn",
+    "owl_verify_attn_phases", "owl_stream_read_probe",
     "owl_build_tree_mask", "owl_build_tree_mask_host", "owl_gather_kv",
     "owl_status_str", "owl_version",
 )
@@ -81,6 +82,11 @@ def lib() -> ctypes.CDLL:
         l.owl_verify_attn.restype = ctypes.c_int
         l.owl_verify_attn.argtypes = [ctypes.POINTER(VerifyDesc), vp, vp, vp, vp, vp, vp, vp,
                                       vp, ctypes.c_size_t, vp, vp]
+        l.owl_verify_attn_phases.restype = ctypes.c_int
+        l.owl_verify_attn_phases.argtypes = [ctypes.POINTER(VerifyDesc), vp, vp, vp, vp, vp, vp, vp,
+                                             vp, ctypes.c_size_t, vp, vp, i32]
+        l.owl_stream_read_probe.restype = ctypes.c_int
+        l.owl_stream_read_probe.argtypes = [vp, ctypes.c_size_t, vp, i32, vp]
         l.owl_build_tree_mask.restype = ctypes.c_int
         l.owl_build_tree_mask.argtypes = [vp, i32, i32, vp, vp, vp, vp]
         l.owl_build_tree_mask_host.restype = ctypes.c_int
@@ -146,6 +152,26 @@ def owl_verify_attn(desc: VerifyDesc, q, k_cache, v_cache, page_table, ctx_lens,
                                _ptr(workspace), ws_bytes, _ptr(dev_status),
                                _stream() if stream is None else stream)
     _check(rc, "owl_verify_attn")
+
+
+PHASE_SPLIT, PHASE_COMBINE, PHASE_ALL = 1, 2, 3
+
+
+def owl_verify_attn_phases(desc: VerifyDesc, q, k_cache, v_cache, page_table, ctx_lens, tree_parent,
+                           out, workspace, dev_status=None, stream: Optional[int] = None,
+                           phases: int = PHASE_ALL) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().owl_verify_attn_phases(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                      _ptr(page_table), _ptr(ctx_lens), _ptr(tree_parent), _ptr(out),
+                                      _ptr(workspace), ws_bytes, _ptr(dev_status),
+                                      _stream() if stream is None else stream, phases)
+    _check(rc, "owl_verify_attn_phases")
+
+
+def owl_stream_read_probe(src, sink, n_workgroups: int, stream: Optional[int] = None) -> None:
+    rc = lib().owl_stream_read_probe(_ptr(src), src.numel() * src.element_size(), _ptr(sink),
+                                     n_workgroups, _stream() if stream is None else stream)
+    _check(rc, "owl_stream_read_probe")
 
 
 def owl_build_tree_mask(tree_parent, anc_mask, depth=None, dev_status=None,

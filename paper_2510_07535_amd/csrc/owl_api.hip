@@ -175,6 +175,17 @@ owl_status owl_verify_attn(const owl_verify_desc *desc, const void *q, const voi
                            void *workspace, size_t workspace_bytes, uint32_t *dev_status,
                            void *stream)
 {
+    return owl_verify_attn_phases(desc, q, k_cache, v_cache, page_table, ctx_lens, tree_parent, out,
+                                  workspace, workspace_bytes, dev_status, stream, OWL_PHASE_ALL);
+}
+
+owl_status owl_verify_attn_phases(const owl_verify_desc *desc, const void *q, const void *k_cache,
+                                  const void *v_cache, const int32_t *page_table,
+                                  const int32_t *ctx_lens, const int32_t *tree_parent, float *out,
+                                  void *workspace, size_t workspace_bytes, uint32_t *dev_status,
+                                  void *stream, int32_t phases)
+{
+    if (phases < 1 || phases > OWL_PHASE_ALL) return OWL_ERR_INVALID_ARG;
     FullPlan fp;
     owl_status st = make_plan(desc, &fp);
     if (st != OWL_OK) return st;
@@ -209,9 +220,12 @@ owl_status owl_verify_attn(const owl_verify_desc *desc, const void *q, const voi
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     dim3 grid(p.max_splits, p.Hkv * p.row_groups, p.B);
-    fp.variant->launch(p, grid, s);
-    if (hipGetLastError() != hipSuccess) return OWL_ERR_HIP;
-    if (launch_combine(p, desc->head_dim, s) != hipSuccess) return OWL_ERR_HIP;
+    if (phases & OWL_PHASE_SPLIT) {
+        fp.variant->launch(p, grid, s);
+        if (hipGetLastError() != hipSuccess) return OWL_ERR_HIP;
+    }
+    if (phases & OWL_PHASE_COMBINE)
+        if (launch_combine(p, desc->head_dim, s) != hipSuccess) return OWL_ERR_HIP;
     return OWL_OK;
 }
 
@@ -254,6 +268,16 @@ owl_status owl_gather_kv(const owl_verify_desc *desc, const void *cache, const i
     if (misaligned(cache, 16) || misaligned(dst, 16)) return OWL_ERR_INVALID_ARG;
     if (launch_gather(*desc, cache, page_table, seq, first_pos, n_tokens, dst, dev_status,
                       static_cast<hipStream_t>(stream)) != hipSuccess)
+        return OWL_ERR_HIP;
+    return OWL_OK;
+}
+
+owl_status owl_stream_read_probe(const void *src, size_t bytes, uint32_t *sink,
+                                 int32_t n_workgroups, void *stream)
+{
+    if (!src || !sink || n_workgroups < 1 || bytes % 16 != 0) return OWL_ERR_INVALID_ARG;
+    if (misaligned(src, 16)) return OWL_ERR_INVALID_ARG;
+    if (launch_stream_read(src, bytes, sink, n_workgroups, static_cast<hipStream_t>(stream)) != hipSuccess)
         return OWL_ERR_HIP;
     return OWL_OK;
 }

@@ -134,4 +134,35 @@ hipError_t launch_gather(const owl_verify_desc &d, const void *cache, const int3
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Streaming-read probe: each workgroup walks the buffer in 4 KiB slabs
+// (256 threads x 16 bytes), workgroups interleaved slab by slab.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) stream_read_kernel(const uint4 *src, size_t n_vec, uint32_t *sink)
+{
+    uint32_t acc = 0;
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n_vec; i += 4 * stride) {
+        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    }
+    for (; i < n_vec; i += stride) {
+        const uint4 a = src[i];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w;
+    }
+    for (int off = 32; off > 0; off >>= 1) acc ^= __shfl_xor(acc, off);
+    __shared__ uint32_t s_acc[4];
+    if ((threadIdx.x & 63) == 0) s_acc[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) sink[blockIdx.x] = s_acc[0] ^ s_acc[1] ^ s_acc[2] ^ s_acc[3];
+}
+
+hipError_t launch_stream_read(const void *src, size_t bytes, uint32_t *sink, int n_wg, hipStream_t s)
+{
+    hipLaunchKernelGGL(stream_read_kernel, dim3(n_wg), dim3(256), 0, s,
+                       static_cast<const uint4 *>(src), bytes / 16, sink);
+    return hipGetLastError();
+}
+
 }  // namespace owl

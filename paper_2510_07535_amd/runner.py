@@ -43,14 +43,18 @@ class VerifyStep:
         self.workspace = torch.empty(max(self.plan.workspace_bytes, 256), dtype=torch.uint8,
                                      device=self.device)
 
-    def run(self, k=None, v=None, page_table=None, stream: Optional[int] = None) -> torch.Tensor:
+    def run(self, k=None, v=None, page_table=None, stream: Optional[int] = None,
+            phases: int = B.PHASE_ALL) -> torch.Tensor:
         """One verify step.  ``k``/``v``/``page_table`` let a caller rotate
-        through several resident copies of the cache."""
-        B.owl_verify_attn(self.desc, self.q, self.k if k is None else k,
-                          self.v if v is None else v,
-                          self.page_table if page_table is None else page_table,
-                          self.ctx_lens, self.tree_parent, self.out, self.workspace, self.status,
-                          stream=stream)
+        through several resident copies of the cache; ``phases`` selects the
+        split-KV pass and/or the combine (measurement only)."""
+        args = (self.desc, self.q, self.k if k is None else k, self.v if v is None else v,
+                self.page_table if page_table is None else page_table,
+                self.ctx_lens, self.tree_parent, self.out, self.workspace, self.status)
+        if phases == B.PHASE_ALL:
+            B.owl_verify_attn(*args, stream=stream)
+        else:
+            B.owl_verify_attn_phases(*args, stream=stream, phases=phases)
         return self.out
 
     def result(self) -> np.ndarray:
