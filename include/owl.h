@@ -85,7 +85,7 @@ typedef struct owl_verify_desc {
     int32_t max_ctx_len;        /* upper bound of ctx_lens[]; sizes the split plan       */
     int32_t qkv_dtype;          /* owl_dtype of q, k_cache, v_cache                      */
     int32_t split_tokens;       /* 0 = let the library choose; else tokens per KV split  */
-                                /* (rounded up to a multiple of 64) -- testing / tuning  */
+                                /* (rounded up to a multiple of 128) -- testing / tuning  */
     float scale;                /* multiplies q.k before the softmax, e.g. 1/sqrt(D)     */
     int32_t reserved_;          /* set to 0                                              */
     int64_t kv_stride_page, kv_stride_head, kv_stride_token;
@@ -198,6 +198,14 @@ owl_status owl_gather_kv(const owl_verify_desc *desc, const void *cache,
  */
 owl_status owl_stream_read_probe(const void *src, size_t bytes, uint32_t *sink,
                                  int32_t n_workgroups, void *stream);
+
+/*
+ * Self-test of the cross-lane step of the in-kernel softmax: one wavefront
+ * reads in64[64] and writes, for every lane l, the maximum over the lanes
+ * {l, l^16, l^32, l^48} (the four lanes that hold the keys of one query row in
+ * a 16x16 MFMA accumulator tile) to out64[64].  Device pointers.
+ */
+owl_status owl_selftest_quad_max(const float *in64, float *out64, void *stream);
 
 /* Static string for a status code. */
 const char *owl_status_str(owl_status s);

@@ -21,7 +21,7 @@ OWL_DEV_BAD_PARENT, OWL_DEV_BAD_PAGE, OWL_DEV_BAD_CTX_LEN = 1, 2, 4
 
 EXPORTS = (
     "owl_verify_attn_plan", "owl_verify_attn_workspace_size", "owl_verify_attn",
-    "owl_verify_attn_phases", "owl_stream_read_probe",
+    "owl_verify_attn_phases", "owl_stream_read_probe", "owl_selftest_quad_max",
     "owl_build_tree_mask", "owl_build_tree_mask_host", "owl_gather_kv",
     "owl_status_str", "owl_version",
 )
@@ -87,6 +87,8 @@ def lib() -> ctypes.CDLL:
                                              vp, ctypes.c_size_t, vp, vp, i32]
         l.owl_stream_read_probe.restype = ctypes.c_int
         l.owl_stream_read_probe.argtypes = [vp, ctypes.c_size_t, vp, i32, vp]
+        l.owl_selftest_quad_max.restype = ctypes.c_int
+        l.owl_selftest_quad_max.argtypes = [vp, vp, vp]
         l.owl_build_tree_mask.restype = ctypes.c_int
         l.owl_build_tree_mask.argtypes = [vp, i32, i32, vp, vp, vp, vp]
         l.owl_build_tree_mask_host.restype = ctypes.c_int
@@ -172,6 +174,11 @@ def owl_stream_read_probe(src, sink, n_workgroups: int, stream: Optional[int] = 
     rc = lib().owl_stream_read_probe(_ptr(src), src.numel() * src.element_size(), _ptr(sink),
                                      n_workgroups, _stream() if stream is None else stream)
     _check(rc, "owl_stream_read_probe")
+
+
+def owl_selftest_quad_max(in64, out64, stream: Optional[int] = None) -> None:
+    rc = lib().owl_selftest_quad_max(_ptr(in64), _ptr(out64), _stream() if stream is None else stream)
+    _check(rc, "owl_selftest_quad_max")
 
 
 def owl_build_tree_mask(tree_parent, anc_mask, depth=None, dev_status=None,

@@ -20,7 +20,7 @@ SOURCES = ["owl_splitkv.hip", "owl_aux.hip", "owl_api.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wno-unused-command-line-argument", "-Wno-unknown-attributes",
+    "-Wno-unused-command-line-argument", "-Wno-unknown-attributes", "-Wno-inline-asm",
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
 ]
 

@@ -69,7 +69,7 @@ owl_status make_plan(const owl_verify_desc *d, FullPlan *fp)
     if (d->qkv_dtype == OWL_F32) {
         tpw = 1; wr = 4; wk = 1; rgs = (RT + 3) / 4;
     } else if (RT <= 2) {
-        tpw = RT; wr = 1; wk = 4; rgs = 1;
+        tpw = 1; wr = 2; wk = 2; rgs = 1;
     } else if (RT <= 4) {
         tpw = 2; wr = 2; wk = 2; rgs = 1;
     } else {
@@ -279,6 +279,13 @@ owl_status owl_stream_read_probe(const void *src, size_t bytes, uint32_t *sink,
     if (misaligned(src, 16)) return OWL_ERR_INVALID_ARG;
     if (launch_stream_read(src, bytes, sink, n_workgroups, static_cast<hipStream_t>(stream)) != hipSuccess)
         return OWL_ERR_HIP;
+    return OWL_OK;
+}
+
+owl_status owl_selftest_quad_max(const float *in64, float *out64, void *stream)
+{
+    if (!in64 || !out64) return OWL_ERR_INVALID_ARG;
+    if (launch_quad_max(in64, out64, static_cast<hipStream_t>(stream)) != hipSuccess) return OWL_ERR_HIP;
     return OWL_OK;
 }
 

@@ -8,6 +8,12 @@
 // the cost of verifying N drafted tokens "hidden" behind the scan of the
 // context (Sec. 1 / Sec. 2 of the paper): the cache is read once whatever N is.
 //
+// Data movement: K/V go from HBM straight into LDS with 128-bit
+// global_load_lds (no VGPR staging), one 16-token page per wavefront and
+// stage, 64 tokens per stage, in a ring of up to 4 stages that is kept full
+// ahead of the compute; readiness is tracked with vmcnt and one barrier per
+// stage.
+//
 // Tile algebra (all MFMA tiles are 16x16, wave64):
 //   S^T[key][row] = K[key][:] . Q[row][:]        A = K fragment, B = Q fragment
 //   O^T[d][row]  += V^T[d][key] * P^T[key][row]  A = V^T fragment, B = P fragment
@@ -70,43 +76,78 @@ __device__ __forceinline__ uint32_t ones2()
     return std::is_same<T, __bf16>::value ? 0x3F803F80u : 0x3C003C00u;
 }
 
+// 16 bytes per lane from global memory straight into LDS: lane l's data lands
+// at lds_addr + 16*l.  lds_addr must be uniform over the wavefront.
+__device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n"
+                 :
+                 : "s"(lds_addr), "v"(gptr)
+                 : "memory", "m0");
+}
+
+// Wait until at most N of this wavefront's vector-memory loads are in flight.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+// max over the four lanes {l, l^16, l^32, l^48}.  permlane32_swap(a, b) trades
+// a's upper 32 lanes against b's lower 32; permlane16_swap trades a's odd
+// 16-lane rows against b's even rows; fed with two copies of x, the two
+// results together hold x and its partner for every lane.
+__device__ __forceinline__ float quad_column_max(float v)
+{
+    const uint32_t x = __builtin_bit_cast(uint32_t, v);
+    auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    const float a = fmaxf(__builtin_bit_cast(float, (uint32_t)r[0]), __builtin_bit_cast(float, (uint32_t)r[1]));
+    const uint32_t y = __builtin_bit_cast(uint32_t, a);
+    auto r2 = __builtin_amdgcn_permlane16_swap(y, y, false, false);
+    return fmaxf(__builtin_bit_cast(float, (uint32_t)r2[0]), __builtin_bit_cast(float, (uint32_t)r2[1]));
+}
+
 // Geometry of one instantiation.
 template <typename T, int D, int TPW, int WR, int WK>
 struct Geo {
     static constexpr bool kF32 = std::is_same<T, float>::value;
     static constexpr int ES = sizeof(T);
-    static constexpr int KSTEPS = WK == 4 ? 4 : 2;      // 32-key steps per LDS stage
-    static constexpr int SK = 32 * KSTEPS;              // keys per stage
+    static constexpr int KSTEPS = 2;                    // 32-key steps per stage
+    static constexpr int SK = 32 * KSTEPS;              // keys per stage: one page per wave
     static constexpr int ROWB = D * ES;                 // bytes of one key row
     static constexpr int PPR = ROWB / 16;               // 16-byte pieces per row
-    static constexpr int LPT = SK * PPR / 256;          // pieces per thread per tensor
+    static constexpr int RPI = 1024 / ROWB;             // key rows per DMA instruction
+    static constexpr int IPP = kPage / RPI;             // DMA instructions per page and tensor
+    static constexpr int LPS = 2 * IPP;                 // DMA instructions per wave and stage
     static constexpr int NT = D / 16;                   // channel tiles of O^T
     static constexpr int STAGE = SK * ROWB;             // bytes per tensor per stage
+    static constexpr int NS = (8 * STAGE <= 131072) ? 4 : ((6 * STAGE <= 131072) ? 3 : 2);
     static constexpr int QREGS = kF32 ? D / 4 : D / 32; // Q fragment slots per tile
-    static constexpr size_t LDS = 4 * (size_t)STAGE + kMaxPagesPerSplit * 4 + 64 * 8 + 64 * 4;
-    static_assert(WR * WK == 4, "four wavefronts per workgroup");
-    static_assert(SK * PPR % 256 == 0, "stage must divide over the workgroup");
-    static_assert((WK - 1) * WR * TPW * (4 * (NT + 1) + 1) * 256 <= 4 * STAGE,
-                  "cross-wave merge buffer must fit in the stage buffers");
+    static constexpr size_t LDS = (size_t)NS * 2 * STAGE + kMaxPagesPerSplit * 4 + 64 * 8 + 64 * 4;
+    static_assert(WR * WK == 4 && (WK == 1 || WK == 2), "four wavefronts per workgroup");
+    static_assert((NS - 1) * LPS < 64, "loads in flight must fit vmcnt");
+    static_assert((WK - 1) * WR * TPW * (4 * (NT + 1) + 1) * 256 <= NS * 2 * STAGE,
+                  "cross-wave merge buffer must fit in the stage ring");
 };
 
 template <typename T, int D, int TPW, int WR, int WK>
-__global__ void __launch_bounds__(256, (TPW <= 2 && !std::is_same<T, float>::value) ? 2 : 1)
-splitkv_kernel(const KParams p)
+__global__ void __launch_bounds__(256) splitkv_kernel(const KParams p)
 {
     using GEO = Geo<T, D, TPW, WR, WK>;
     constexpr bool kF32 = GEO::kF32;
     constexpr int ES = GEO::ES, KSTEPS = GEO::KSTEPS, SK = GEO::SK, ROWB = GEO::ROWB;
-    constexpr int PPR = GEO::PPR, LPT = GEO::LPT, NT = GEO::NT, STAGE = GEO::STAGE;
+    constexpr int PPR = GEO::PPR, NT = GEO::NT, STAGE = GEO::STAGE, NS = GEO::NS;
+    constexpr int RPI = GEO::RPI, IPP = GEO::IPP, LPS = GEO::LPS;
     constexpr int QREGS = GEO::QREGS;
     constexpr int SWZ = (PPR - 1) & 15;
 
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char *Ks = smem;
-    unsigned char *Vs = smem + 2 * STAGE;
-    int32_t *s_pages = reinterpret_cast<int32_t *>(smem + 4 * STAGE);
+    int32_t *s_pages = reinterpret_cast<int32_t *>(smem + NS * 2 * STAGE);
     uint64_t *s_anc = reinterpret_cast<uint64_t *>(s_pages + kMaxPagesPerSplit);
     int32_t *s_parent = reinterpret_cast<int32_t *>(s_anc + 64);
+    const uint32_t lds0 =
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wr = wave % WR, wk = wave / WR;
@@ -137,6 +178,37 @@ splitkv_kernel(const KParams p)
         if (tid < p.N) s_anc[tid] = ancestor_set(s_parent, tid, nullptr, p.dev_status);
     }
     __syncthreads();
+
+    // ---- stage issue: wave w brings page 4*s + w of the split into the ring ----
+    // Lane l of DMA instruction `it` carries piece l % PPR of slot it*RPI + l / PPR.
+    // K rows are stored with their 16-byte pieces XOR-permuted by the slot number
+    // (the permutation is applied to the global address, the LDS side of the
+    // transfer is always lane-linear), V rows as they are.  Slots past the end
+    // of the split (ragged last stage only) re-read the last valid row: finite
+    // data whose scores are masked out later.
+    const unsigned char *kbase = static_cast<const unsigned char *>(p.k);
+    const unsigned char *vbase = static_cast<const unsigned char *>(p.v);
+    const int last_pgx = (pos1 - 1 - pos0) >> 4, last_slot = (pos1 - 1) & (kPage - 1);
+    const int ld_piece = lane % PPR, ld_row = lane / PPR;
+    const int64_t head_off = (int64_t)g * p.stride_head * ES;
+    const int64_t tok_bytes = p.stride_token * ES;
+
+    auto issue_stage = [&](int s) {
+        const int buf = s % NS;
+        const int pgx_raw = s * (SK / kPage) + wave;
+        const int pgx = min(pgx_raw, last_pgx);
+        const int slot_max = pgx_raw >= last_pgx ? last_slot : kPage - 1;
+        const int64_t base = (int64_t)s_pages[pgx] * p.stride_page * ES + head_off;
+        const uint32_t lds_k = lds0 + buf * 2 * STAGE + wave * kPage * ROWB;
+#pragma unroll
+        for (int it = 0; it < IPP; ++it) {
+            const int row = it * RPI + ld_row;
+            const int64_t off = base + min(row, slot_max) * tok_bytes;
+            const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_k + it * RPI * ROWB);
+            dma16(kbase + off + ((ld_piece ^ (row & SWZ)) << 4), dst);
+            dma16(vbase + off + (ld_piece << 4), dst + STAGE);
+        }
+    };
 
     // ---- this wave's query rows ----
     uint4 qf[TPW][kF32 ? 1 : QREGS];
@@ -175,40 +247,6 @@ splitkv_kernel(const KParams p)
         for (int u = 0; u <= NT; ++u) O[t][u] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // ---- stage loads: global -> registers -> LDS ----
-    const unsigned char *kbase = static_cast<const unsigned char *>(p.k);
-    const unsigned char *vbase = static_cast<const unsigned char *>(p.v);
-    uint4 kreg[LPT], vreg[LPT];
-
-    auto load_stage = [&](int s) {
-        const int sbase = pos0 + s * SK;
-#pragma unroll
-        for (int it = 0; it < LPT; ++it) {
-            const int id = it * 256 + tid;
-            const int key = id / PPR, piece = id % PPR;
-            const int pos = sbase + key;
-            if (pos < pos1) {
-                const int64_t pg = s_pages[(pos - pos0) >> 4];
-                const int64_t off = (pg * p.stride_page + (int64_t)g * p.stride_head +
-                                     (int64_t)(pos & (kPage - 1)) * p.stride_token) * ES + piece * 16;
-                kreg[it] = *reinterpret_cast<const uint4 *>(kbase + off);
-                vreg[it] = *reinterpret_cast<const uint4 *>(vbase + off);
-            } else {
-                kreg[it] = make_uint4(0, 0, 0, 0);   // keys past the end: finite, masked later
-                vreg[it] = make_uint4(0, 0, 0, 0);
-            }
-        }
-    };
-    auto store_stage = [&](int buf) {
-#pragma unroll
-        for (int it = 0; it < LPT; ++it) {
-            const int id = it * 256 + tid;
-            const int key = id / PPR, piece = id % PPR;
-            *reinterpret_cast<uint4 *>(Ks + buf * STAGE + key * ROWB + ((piece ^ (key & SWZ)) << 4)) = kreg[it];
-            *reinterpret_cast<uint4 *>(Vs + buf * STAGE + key * ROWB + (piece << 4)) = vreg[it];
-        }
-    };
-
     // ---- softmax of one row tile over one 32-key step ----
     auto softmax_step = [&](f32x4 &s0, f32x4 &s1, int t, int step_pos, bool masked) {
         if (masked) {
@@ -225,8 +263,7 @@ splitkv_kernel(const KParams p)
         }
         float tm = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
                          fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
-        tm = fmaxf(tm, __shfl_xor(tm, 16));
-        tm = fmaxf(tm, __shfl_xor(tm, 32));
+        tm = quad_column_max(tm);
         const float sc = tm * p.c_log2;
         if (__builtin_amdgcn_ballot_w64(sc > m[t] + kTau) != 0) {   // uniform over the wave
             const float mn = fmaxf(m[t], sc);
@@ -242,10 +279,10 @@ splitkv_kernel(const KParams p)
         }
     };
 
-    // ---- one 32-key step of a stage held in LDS buffer `buf` ----
+    // ---- one 32-key step of the stage held in ring slot `buf` ----
     auto compute_step = [&](int buf, int ks, int step_pos) {
-        const unsigned char *Kb = Ks + buf * STAGE + ks * 32 * ROWB;
-        const unsigned char *Vb = Vs + buf * STAGE + ks * 32 * ROWB;
+        const unsigned char *Kb = smem + buf * 2 * STAGE + ks * 32 * ROWB;
+        const unsigned char *Vb = Kb + STAGE;
         const bool masked = step_pos + 32 > L;       // reaches drafts or the ragged end
         if constexpr (kF32) {
             // fp32 path: 16x16x4 MFMA, one channel per quad and step
@@ -276,8 +313,8 @@ splitkv_kernel(const KParams p)
 #pragma unroll
                     for (int kk = 0; kk < QREGS; ++kk)
                         s0 = __builtin_amdgcn_mfma_f32_16x16x4f32(kf[kk], qs[t][kk], s0, 0, 0, 0);
-                    // the second half-tile of the step is handled by the kt loop:
-                    // feed a fully masked dummy so the softmax sees 16 keys only
+                    // the other 16 keys of the step come with the next kt: give
+                    // the softmax a fully masked second half
                     f32x4 s1 = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
                     softmax_step(s0, s1, t, step_pos + kt * 16, masked);
 #pragma unroll
@@ -346,27 +383,39 @@ splitkv_kernel(const KParams p)
         }
     };
 
-    // ---- main loop: double-buffered stages ----
-    load_stage(0);
-    store_stage(0);
-    __syncthreads();
+    // ---- main loop: keep NS-1 stages in flight ahead of the one computed ----
+    int issued = 0;
+    for (; issued < NS - 1 && issued < nstages; ++issued) issue_stage(issued);
     for (int s = 0; s < nstages; ++s) {
-        const int buf = s & 1;
-        const bool more = s + 1 < nstages;
-        if (more) load_stage(s + 1);
+        // stage s has landed once at most (younger stages) * LPS loads remain
+        const int ahead = issued - (s + 1);
+        if constexpr (NS > 3) {
+            if (ahead >= 2) wait_vmcnt<2 * LPS>();
+            else if (ahead == 1) wait_vmcnt<LPS>();
+            else wait_vmcnt<0>();
+        } else if constexpr (NS > 2) {
+            if (ahead >= 1) wait_vmcnt<LPS>();
+            else wait_vmcnt<0>();
+        } else {
+            wait_vmcnt<0>();
+        }
+        __syncthreads();     // everyone's part of stage s is in; stage s-1 is fully consumed
+        if (issued < nstages) {
+            issue_stage(issued);                    // refills the slot stage s-1 occupied
+            ++issued;
+        }
         const int sbase = pos0 + s * SK;
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
             if (ks % WK != wk) continue;
             if (sbase + ks * 32 >= pos1) continue;   // uniform: nothing left in this step
-            compute_step(buf, ks, sbase + ks * 32);
+            compute_step(s % NS, ks, sbase + ks * 32);
         }
-        if (more) store_stage(buf ^ 1);
-        __syncthreads();
     }
 
-    // ---- merge the key groups of a row group through LDS (reuses the stages) ----
+    // ---- merge the key groups of a row group through LDS (reuses the ring) ----
     if constexpr (WK > 1) {
+        __syncthreads();
         float *mb = reinterpret_cast<float *>(smem);
         constexpr int PER_TILE = 4 * (NT + 1) + 1;
         if (wk > 0) {
@@ -423,6 +472,20 @@ splitkv_kernel(const KParams p)
 }
 
 // ---------------------------------------------------------------------------
+// A one-wavefront check of quad_column_max's lane semantics (test hook).
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(64) quad_max_kernel(const float *in, float *out)
+{
+    out[threadIdx.x] = quad_column_max(in[threadIdx.x]);
+}
+
+hipError_t launch_quad_max(const float *in, float *out, hipStream_t s)
+{
+    hipLaunchKernelGGL(quad_max_kernel, dim3(1), dim3(64), 0, s, in, out);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // instantiations
 // ---------------------------------------------------------------------------
 template <typename T, int D, int TPW, int WR, int WK>
@@ -438,10 +501,9 @@ static void launch_variant(const KParams &p, dim3 grid, hipStream_t s)
               reinterpret_cast<const void *>(&splitkv_kernel<T, D, TPW, WR, WK>) }
 
 #define OWL_VARIANTS_16BIT(DT, T, D)                                                    \
-    OWL_VARIANT(DT, T, D, 1, 1, 4), OWL_VARIANT(DT, T, D, 2, 1, 4),                     \
-    OWL_VARIANT(DT, T, D, 2, 2, 2), OWL_VARIANT(DT, T, D, 2, 4, 1),                     \
-    OWL_VARIANT(DT, T, D, 3, 4, 1), OWL_VARIANT(DT, T, D, 4, 4, 1),                     \
-    OWL_VARIANT(DT, T, D, 5, 4, 1)
+    OWL_VARIANT(DT, T, D, 1, 2, 2), OWL_VARIANT(DT, T, D, 2, 2, 2),                     \
+    OWL_VARIANT(DT, T, D, 2, 4, 1), OWL_VARIANT(DT, T, D, 3, 4, 1),                     \
+    OWL_VARIANT(DT, T, D, 4, 4, 1), OWL_VARIANT(DT, T, D, 5, 4, 1)
 
 static const Variant kVariants[] = {
     OWL_VARIANTS_16BIT(OWL_BF16, __bf16, 128),

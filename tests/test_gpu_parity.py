@@ -181,6 +181,21 @@ def test_zero_query_integer_values_exact_mean():
             assert np.array_equal(got[0, N - 1, h].astype(np.float64), want[h // 2]), split
 
 
+def test_quad_max_lane_semantics():
+    """The softmax's cross-lane maximum must cover exactly lanes l, l^16, l^32,
+    l^48 (a wrong exchange would still give finite, nearly right outputs, so
+    it is pinned here on its own)."""
+    r = _rng(77)
+    for _ in range(4):
+        x = r.standard_normal(64).astype(np.float32)
+        dx = torch.from_numpy(x).cuda()
+        dy = torch.empty(64, dtype=torch.float32, device="cuda")
+        B.owl_selftest_quad_max(dx, dy)
+        torch.cuda.synchronize()
+        want = x.reshape(4, 16).max(axis=0)
+        assert np.array_equal(dy.cpu().numpy(), np.tile(want, 4))
+
+
 # ---------------------------------------------------------------------------
 # mask builder and paging: bit-exact
 # ---------------------------------------------------------------------------
