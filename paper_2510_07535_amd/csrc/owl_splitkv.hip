@@ -247,9 +247,105 @@ __global__ void __launch_bounds__(256) splitkv_kernel(const KParams p)
         for (int u = 0; u <= NT; ++u) O[t][u] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // ---- softmax of one row tile over one 32-key step ----
-    auto softmax_step = [&](f32x4 &s0, f32x4 &s1, int t, int step_pos, bool masked) {
-        if (masked) {
+    // ---- fragment loads of one 32-key step (16-bit types) ----
+    // K: 2 key tiles x D/32 contraction steps.  V: NT contiguous channels of 8
+    // keys per lane, then a 16-bit transpose in registers.
+    auto load_kv_frags = [&](const unsigned char *Kb, const unsigned char *Vb, uint4 (&kf)[2][QREGS],
+                             uint4 (&vf)[NT]) {
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt) {
+            const int key = kt * 16 + j;
+#pragma unroll
+            for (int kk = 0; kk < QREGS; ++kk)
+                kf[kt][kk] = *reinterpret_cast<const uint4 *>(
+                    Kb + key * ROWB + (((4 * kk + qd) ^ (key & SWZ)) << 4));
+        }
+        uint32_t vraw[8][NT / 2];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int vkey = (e < 4) ? 4 * qd + e : 16 + 4 * qd + (e - 4);
+            const unsigned char *src = Vb + vkey * ROWB + j * NT * 2;
+            if constexpr (NT == 8) {
+                const uint4 x = *reinterpret_cast<const uint4 *>(src);
+                vraw[e][0] = x.x; vraw[e][1] = x.y; vraw[e][2] = x.z; vraw[e][3] = x.w;
+            } else {
+                const uint2 x = *reinterpret_cast<const uint2 *>(src);
+                vraw[e][0] = x.x; vraw[e][1] = x.y;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < NT; ++u) {
+            const uint32_t sel = (u & 1) ? 0x07060302u : 0x05040100u;
+            vf[u].x = __builtin_amdgcn_perm(vraw[1][u / 2], vraw[0][u / 2], sel);
+            vf[u].y = __builtin_amdgcn_perm(vraw[3][u / 2], vraw[2][u / 2], sel);
+            vf[u].z = __builtin_amdgcn_perm(vraw[5][u / 2], vraw[4][u / 2], sel);
+            vf[u].w = __builtin_amdgcn_perm(vraw[7][u / 2], vraw[6][u / 2], sel);
+        }
+    };
+
+    // ---- fast step: no mask, fixed reference m, accumulators touched by MFMA only ----
+    // p = 2^(x - m) is exact in relative terms whatever m is; with m frozen at
+    // the first step's row maximum, p overflows only if a later score exceeds
+    // it by more than ~100 (log2 units), which the row sum exposes afterwards.
+    auto fast_step = [&](int buf, int ks) {
+        if constexpr (!kF32) {
+            const unsigned char *Kb = smem + buf * 2 * STAGE + ks * 32 * ROWB;
+            uint4 kf[2][QREGS], vf[NT];
+            load_kv_frags(Kb, Kb + STAGE, kf, vf);
+            const uint4 ones = make_uint4(ones2<T>(), ones2<T>(), ones2<T>(), ones2<T>());
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) {
+                f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < QREGS; ++kk) {
+                    s0 = mfma16<T>(kf[0][kk], qf[t][kk], s0);
+                    s1 = mfma16<T>(kf[1][kk], qf[t][kk], s1);
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    s0[r] = fast_exp2(__builtin_fmaf(s0[r], p.c_log2, -m[t]));
+                    s1[r] = fast_exp2(__builtin_fmaf(s1[r], p.c_log2, -m[t]));
+                }
+                uint4 pf;
+                pf.x = pack2<T>(s0[0], s0[1]);
+                pf.y = pack2<T>(s0[2], s0[3]);
+                pf.z = pack2<T>(s1[0], s1[1]);
+                pf.w = pack2<T>(s1[2], s1[3]);
+#pragma unroll
+                for (int u = 0; u < NT; ++u) O[t][u] = mfma16<T>(vf[u], pf, O[t][u]);
+                O[t][NT] = mfma16<T>(ones, pf, O[t][NT]);
+            }
+        }
+    };
+
+    // ---- reference m of every row tile from one unmasked step (before the fast loop) ----
+    auto init_reference = [&](int buf, int ks) {
+        if constexpr (!kF32) {
+            const unsigned char *Kb = smem + buf * 2 * STAGE + ks * 32 * ROWB;
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) {
+                f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt) {
+                    const int key = kt * 16 + j;
+#pragma unroll
+                    for (int kk = 0; kk < QREGS; ++kk) {
+                        const uint4 kfr = *reinterpret_cast<const uint4 *>(
+                            Kb + key * ROWB + (((4 * kk + qd) ^ (key & SWZ)) << 4));
+                        if (kt == 0) s0 = mfma16<T>(kfr, qf[t][kk], s0);
+                        else s1 = mfma16<T>(kfr, qf[t][kk], s1);
+                    }
+                }
+                float tm = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
+                                 fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
+                m[t] = quad_column_max(tm) * p.c_log2;
+            }
+        }
+    };
+
+    // ---- careful softmax of one row tile over one 32-key step: mask + exact online rescale ----
+    auto softmax_step = [&](f32x4 &s0, f32x4 &s1, int t, int step_pos) {
+        if (step_pos + 32 > L) {                     // reaches drafts or the ragged end (uniform)
             uint64_t anc = ~(uint64_t)0;
             if (has_drafts && irow[t] >= 0) anc = s_anc[irow[t]];
 #pragma unroll
@@ -265,7 +361,7 @@ __global__ void __launch_bounds__(256) splitkv_kernel(const KParams p)
                          fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
         tm = quad_column_max(tm);
         const float sc = tm * p.c_log2;
-        if (__builtin_amdgcn_ballot_w64(sc > m[t] + kTau) != 0) {   // uniform over the wave
+        if (__builtin_amdgcn_ballot_w64(sc > m[t]) != 0) {          // uniform over the wave
             const float mn = fmaxf(m[t], sc);
             const float alpha = fast_exp2(m[t] - mn);
             m[t] = mn;
@@ -279,11 +375,10 @@ __global__ void __launch_bounds__(256) splitkv_kernel(const KParams p)
         }
     };
 
-    // ---- one 32-key step of the stage held in ring slot `buf` ----
-    auto compute_step = [&](int buf, int ks, int step_pos) {
+    // ---- careful step: any step, any type ----
+    auto careful_step = [&](int buf, int ks, int step_pos) {
         const unsigned char *Kb = smem + buf * 2 * STAGE + ks * 32 * ROWB;
         const unsigned char *Vb = Kb + STAGE;
-        const bool masked = step_pos + 32 > L;       // reaches drafts or the ragged end
         if constexpr (kF32) {
             // fp32 path: 16x16x4 MFMA, one channel per quad and step
 #pragma unroll
@@ -316,7 +411,7 @@ __global__ void __launch_bounds__(256) splitkv_kernel(const KParams p)
                     // the other 16 keys of the step come with the next kt: give
                     // the softmax a fully masked second half
                     f32x4 s1 = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-                    softmax_step(s0, s1, t, step_pos + kt * 16, masked);
+                    softmax_step(s0, s1, t, step_pos + kt * 16);
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
 #pragma unroll
@@ -327,39 +422,8 @@ __global__ void __launch_bounds__(256) splitkv_kernel(const KParams p)
                 }
             }
         } else {
-            // K fragments: 2 key tiles x D/32 contraction steps
-            uint4 kf[2][QREGS];
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt) {
-                const int key = kt * 16 + j;
-#pragma unroll
-                for (int kk = 0; kk < QREGS; ++kk)
-                    kf[kt][kk] = *reinterpret_cast<const uint4 *>(
-                        Kb + key * ROWB + (((4 * kk + qd) ^ (key & SWZ)) << 4));
-            }
-            // V: NT contiguous channels of 8 keys per lane, then a 16-bit transpose
-            uint32_t vraw[8][NT / 2];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int vkey = (e < 4) ? 4 * qd + e : 16 + 4 * qd + (e - 4);
-                const unsigned char *src = Vb + vkey * ROWB + j * NT * 2;
-                if constexpr (NT == 8) {
-                    const uint4 x = *reinterpret_cast<const uint4 *>(src);
-                    vraw[e][0] = x.x; vraw[e][1] = x.y; vraw[e][2] = x.z; vraw[e][3] = x.w;
-                } else {
-                    const uint2 x = *reinterpret_cast<const uint2 *>(src);
-                    vraw[e][0] = x.x; vraw[e][1] = x.y;
-                }
-            }
-            uint4 vf[NT];
-#pragma unroll
-            for (int u = 0; u < NT; ++u) {
-                const uint32_t sel = (u & 1) ? 0x07060302u : 0x05040100u;
-                vf[u].x = __builtin_amdgcn_perm(vraw[1][u / 2], vraw[0][u / 2], sel);
-                vf[u].y = __builtin_amdgcn_perm(vraw[3][u / 2], vraw[2][u / 2], sel);
-                vf[u].z = __builtin_amdgcn_perm(vraw[5][u / 2], vraw[4][u / 2], sel);
-                vf[u].w = __builtin_amdgcn_perm(vraw[7][u / 2], vraw[6][u / 2], sel);
-            }
+            uint4 kf[2][QREGS], vf[NT];
+            load_kv_frags(Kb, Vb, kf, vf);
             const uint4 ones = make_uint4(ones2<T>(), ones2<T>(), ones2<T>(), ones2<T>());
 #pragma unroll
             for (int t = 0; t < TPW; ++t) {
@@ -370,7 +434,7 @@ __global__ void __launch_bounds__(256) splitkv_kernel(const KParams p)
                     s0 = mfma16<T>(kf[0][kk], qf[t][kk], s0);
                     s1 = mfma16<T>(kf[1][kk], qf[t][kk], s1);
                 }
-                softmax_step(s0, s1, t, step_pos, masked);
+                softmax_step(s0, s1, t, step_pos);
                 uint4 pf;
                 pf.x = pack2<T>(s0[0], s0[1]);
                 pf.y = pack2<T>(s0[2], s0[3]);
@@ -383,10 +447,9 @@ __global__ void __launch_bounds__(256) splitkv_kernel(const KParams p)
         }
     };
 
-    // ---- main loop: keep NS-1 stages in flight ahead of the one computed ----
+    // ---- stage loop skeleton: keep NS-1 stages in flight ahead of the one computed ----
     int issued = 0;
-    for (; issued < NS - 1 && issued < nstages; ++issued) issue_stage(issued);
-    for (int s = 0; s < nstages; ++s) {
+    auto wait_stage = [&](int s) {
         // stage s has landed once at most (younger stages) * LPS loads remain
         const int ahead = issued - (s + 1);
         if constexpr (NS > 3) {
@@ -399,17 +462,61 @@ __global__ void __launch_bounds__(256) splitkv_kernel(const KParams p)
         } else {
             wait_vmcnt<0>();
         }
-        __syncthreads();     // everyone's part of stage s is in; stage s-1 is fully consumed
-        if (issued < nstages) {
-            issue_stage(issued);                    // refills the slot stage s-1 occupied
-            ++issued;
-        }
-        const int sbase = pos0 + s * SK;
+    };
+    auto run_stages = [&](int s_begin, int s_end, auto fast_tag) {
+        for (int s = s_begin; s < s_end; ++s) {
+            wait_stage(s);
+            __syncthreads();     // everyone's part of stage s is in; stage s-1 is fully consumed
+            if (issued < nstages) {
+                issue_stage(issued);                // refills the slot stage s-1 occupied
+                ++issued;
+            }
+            const int sbase = pos0 + s * SK;
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) {
-            if (ks % WK != wk) continue;
-            if (sbase + ks * 32 >= pos1) continue;   // uniform: nothing left in this step
-            compute_step(s % NS, ks, sbase + ks * 32);
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                if (ks % WK != wk) continue;
+                if constexpr (decltype(fast_tag)::value) {
+                    fast_step(s % NS, ks);
+                } else {
+                    if (sbase + ks * 32 >= pos1) continue;   // uniform: nothing left in this step
+                    careful_step(s % NS, ks, sbase + ks * 32);
+                }
+            }
+        }
+    };
+
+    // The Q fragments must have arrived before the first DMA is issued: from
+    // here on vmcnt counts DMA stages only.
+    wait_vmcnt<0>();
+
+    // Pass 0: stages that lie wholly inside the prefix run the fast step with a
+    // frozen reference; the rest (drafts, ragged end) run the careful step.
+    // Pass 1 happens only if a row sum of pass 0 is not a modest finite number:
+    // the whole split is redone with the careful step.  bf16 only: an fp16 P
+    // cannot hold 2^(x - m) for a stale m, fp32 is the small correctness shape.
+    constexpr bool kHasFast = std::is_same<T, __bf16>::value;
+    for (int pass = 0; pass < 2; ++pass) {
+        issued = 0;
+        for (; issued < NS - 1 && issued < nstages; ++issued) issue_stage(issued);
+        int n_fast = 0;
+        if (kHasFast && pass == 0) n_fast = max(0, min(nstages, (L - pos0) / SK));
+        if (n_fast > 0) {
+            wait_stage(0);
+            __syncthreads();
+            init_reference(0, wk);
+            run_stages(0, n_fast, std::true_type{});
+        }
+        run_stages(n_fast, nstages, std::false_type{});
+        if (!kHasFast || pass == 1) break;
+        bool bad = false;
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) bad |= !(O[t][NT][0] < 1.0e30f);
+        if (!__syncthreads_or(bad ? 1 : 0)) break;
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+            m[t] = kMInit;
+#pragma unroll
+            for (int u = 0; u <= NT; ++u) O[t][u] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
     }
 
