@@ -200,6 +200,16 @@ owl_status owl_stream_read_probe(const void *src, size_t bytes, uint32_t *sink,
                                  int32_t n_workgroups, void *stream);
 
 /*
+ * Measurement aid: like owl_stream_read_probe, but the buffer is read in
+ * 4 KiB blocks in the order block_order[0 .. n_blocks-1] (device int32, every
+ * entry in [0, buffer bytes / 4096)).  With a random order this is the access
+ * pattern of a head-major cache with 16-token pages of 128 bf16 channels
+ * handed out at random, and its GB/s is the ceiling for that layout.
+ */
+owl_status owl_gather_read_probe(const void *src, const int32_t *block_order, int32_t n_blocks,
+                                 uint32_t *sink, int32_t n_workgroups, void *stream);
+
+/*
  * Self-test of the cross-lane step of the in-kernel softmax: one wavefront
  * reads in64[64] and writes, for every lane l, the maximum over the lanes
  * {l, l^16, l^32, l^48} (the four lanes that hold the keys of one query row in

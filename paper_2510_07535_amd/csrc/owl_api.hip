@@ -282,6 +282,17 @@ owl_status owl_stream_read_probe(const void *src, size_t bytes, uint32_t *sink,
     return OWL_OK;
 }
 
+owl_status owl_gather_read_probe(const void *src, const int32_t *block_order, int32_t n_blocks,
+                                 uint32_t *sink, int32_t n_workgroups, void *stream)
+{
+    if (!src || !block_order || !sink || n_blocks < 1 || n_workgroups < 1) return OWL_ERR_INVALID_ARG;
+    if (misaligned(src, 16)) return OWL_ERR_INVALID_ARG;
+    if (launch_gather_read(src, block_order, n_blocks, sink, n_workgroups,
+                           static_cast<hipStream_t>(stream)) != hipSuccess)
+        return OWL_ERR_HIP;
+    return OWL_OK;
+}
+
 owl_status owl_selftest_quad_max(const float *in64, float *out64, void *stream)
 {
     if (!in64 || !out64) return OWL_ERR_INVALID_ARG;

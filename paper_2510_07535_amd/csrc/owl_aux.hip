@@ -158,6 +158,42 @@ __global__ void __launch_bounds__(256) stream_read_kernel(const uint4 *src, size
     if (threadIdx.x == 0) sink[blockIdx.x] = s_acc[0] ^ s_acc[1] ^ s_acc[2] ^ s_acc[3];
 }
 
+// Same, but the buffer is visited in 4 KiB blocks in the order given by
+// `perm` (one block = 256 threads x 16 bytes), eight blocks in flight per
+// workgroup: the access pattern of a head-major paged cache whose pages were
+// handed out in random order.
+__global__ void __launch_bounds__(256) gather_read_kernel(const uint4 *src, const int32_t *perm,
+                                                          int n_blocks, uint32_t *sink)
+{
+    uint32_t acc = 0;
+    int blk = blockIdx.x;
+    const int stride = gridDim.x;
+    for (; blk + 7 * stride < n_blocks; blk += 8 * stride) {
+        uint4 v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = src[(size_t)perm[blk + i * stride] * 256 + threadIdx.x];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc ^= v[i].x ^ v[i].y ^ v[i].z ^ v[i].w;
+    }
+    for (; blk < n_blocks; blk += stride) {
+        const uint4 a = src[(size_t)perm[blk] * 256 + threadIdx.x];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w;
+    }
+    for (int off = 32; off > 0; off >>= 1) acc ^= __shfl_xor(acc, off);
+    __shared__ uint32_t s_acc[4];
+    if ((threadIdx.x & 63) == 0) s_acc[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) sink[blockIdx.x] = s_acc[0] ^ s_acc[1] ^ s_acc[2] ^ s_acc[3];
+}
+
+hipError_t launch_gather_read(const void *src, const int32_t *perm, int n_blocks, uint32_t *sink,
+                              int n_wg, hipStream_t s)
+{
+    hipLaunchKernelGGL(gather_read_kernel, dim3(n_wg), dim3(256), 0, s,
+                       static_cast<const uint4 *>(src), perm, n_blocks, sink);
+    return hipGetLastError();
+}
+
 hipError_t launch_stream_read(const void *src, size_t bytes, uint32_t *sink, int n_wg, hipStream_t s)
 {
     hipLaunchKernelGGL(stream_read_kernel, dim3(n_wg), dim3(256), 0, s,

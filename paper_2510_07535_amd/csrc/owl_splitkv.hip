@@ -126,7 +126,7 @@ struct Geo {
     static constexpr int QREGS = kF32 ? D / 4 : D / 32; // Q fragment slots per tile
     static constexpr size_t LDS = (size_t)NS * 2 * STAGE + kMaxPagesPerSplit * 4 + 64 * 8 + 64 * 4;
     static_assert(WR * WK == 4 && (WK == 1 || WK == 2), "four wavefronts per workgroup");
-    static_assert((NS - 1) * LPS < 64, "loads in flight must fit vmcnt");
+    static_assert(NS * LPS < 64, "loads in flight must fit vmcnt");
     static_assert((WK - 1) * WR * TPW * (4 * (NT + 1) + 1) * 256 <= NS * 2 * STAGE,
                   "cross-wave merge buffer must fit in the stage ring");
 };
@@ -452,22 +452,16 @@ __global__ void __launch_bounds__(256) splitkv_kernel(const KParams p)
     auto wait_stage = [&](int s) {
         // stage s has landed once at most (younger stages) * LPS loads remain
         const int ahead = issued - (s + 1);
-        if constexpr (NS > 3) {
-            if (ahead >= 2) wait_vmcnt<2 * LPS>();
-            else if (ahead == 1) wait_vmcnt<LPS>();
-            else wait_vmcnt<0>();
-        } else if constexpr (NS > 2) {
-            if (ahead >= 1) wait_vmcnt<LPS>();
-            else wait_vmcnt<0>();
-        } else {
-            wait_vmcnt<0>();
-        }
+        if (NS > 3 && ahead >= 3) wait_vmcnt<(NS > 3 ? 3 : 0) * LPS>();
+        else if (NS > 2 && ahead == 2) wait_vmcnt<(NS > 2 ? 2 : 0) * LPS>();
+        else if (NS > 1 && ahead == 1) wait_vmcnt<LPS>();
+        else wait_vmcnt<0>();
     };
     auto run_stages = [&](int s_begin, int s_end, auto fast_tag) {
         for (int s = s_begin; s < s_end; ++s) {
             wait_stage(s);
             __syncthreads();     // everyone's part of stage s is in; stage s-1 is fully consumed
-            if (issued < nstages) {
+            if (issued < nstages && issued <= s + NS - 1) {
                 issue_stage(issued);                // refills the slot stage s-1 occupied
                 ++issued;
             }
@@ -482,6 +476,152 @@ __global__ void __launch_bounds__(256) splitkv_kernel(const KParams p)
                     careful_step(s % NS, ks, sbase + ks * 32);
                 }
             }
+        }
+    };
+
+    // ---- software-pipelined fast loop (two or more row tiles per wave) ----
+    // The wave walks its 32-key steps tile by tile; slot (step j, tile t) holds
+    // three mutually independent pieces so that the matrix pipe and the vector
+    // ALU can run side by side inside ONE wavefront:
+    //     MFMA : O[prev tile] += V^T P(prev)      and   S(next tile) = K Q^T
+    //     VALU : P(this tile) = 2^(S - m), packed to bf16
+    //     LDS  : K fragments / raw V rows of the NEXT step
+    // "next" wraps into the following step (whose K fragments sit in the other
+    // half of a double buffer), so the pipeline never drains inside the loop.
+    // The barrier that admits stage s+1 is taken at the start of the last step
+    // this wave has in stage s; by then all of the wave's LDS reads of stage s
+    // have completed, so stage s+NS is issued into that slot right away.
+    auto run_fast_pipelined = [&](int n_fast) {
+        if constexpr (!kF32 && TPW >= 2) {
+            const int J = (WK == 2) ? n_fast : 2 * n_fast;       // this wave's steps
+            auto step_base = [&](int jj) -> const unsigned char * {
+                const int sj = (WK == 2) ? jj : (jj >> 1);
+                const int ks = (WK == 2) ? wk : (jj & 1);
+                return smem + (sj % NS) * 2 * STAGE + ks * 32 * ROWB;
+            };
+            auto load_k = [&](const unsigned char *Kb, uint4 (&kf)[2][QREGS]) {
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt) {
+                    const int key = kt * 16 + j;
+#pragma unroll
+                    for (int kk = 0; kk < QREGS; ++kk)
+                        kf[kt][kk] = *reinterpret_cast<const uint4 *>(
+                            Kb + key * ROWB + (((4 * kk + qd) ^ (key & SWZ)) << 4));
+                }
+            };
+            auto load_vraw = [&](const unsigned char *Vb, uint32_t (&vraw)[8][NT / 2]) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int vkey = (e < 4) ? 4 * qd + e : 16 + 4 * qd + (e - 4);
+                    const unsigned char *src = Vb + vkey * ROWB + j * NT * 2;
+                    if constexpr (NT == 8) {
+                        const uint4 x = *reinterpret_cast<const uint4 *>(src);
+                        vraw[e][0] = x.x; vraw[e][1] = x.y; vraw[e][2] = x.z; vraw[e][3] = x.w;
+                    } else {
+                        const uint2 x = *reinterpret_cast<const uint2 *>(src);
+                        vraw[e][0] = x.x; vraw[e][1] = x.y;
+                    }
+                }
+            };
+            auto make_vf = [&](const uint32_t (&vraw)[8][NT / 2], uint4 (&vf)[NT]) {
+#pragma unroll
+                for (int u = 0; u < NT; ++u) {
+                    const uint32_t sel = (u & 1) ? 0x07060302u : 0x05040100u;
+                    vf[u].x = __builtin_amdgcn_perm(vraw[1][u / 2], vraw[0][u / 2], sel);
+                    vf[u].y = __builtin_amdgcn_perm(vraw[3][u / 2], vraw[2][u / 2], sel);
+                    vf[u].z = __builtin_amdgcn_perm(vraw[5][u / 2], vraw[4][u / 2], sel);
+                    vf[u].w = __builtin_amdgcn_perm(vraw[7][u / 2], vraw[6][u / 2], sel);
+                }
+            };
+            auto scores = [&](const uint4 (&kf)[2][QREGS], int t, f32x4 &s0, f32x4 &s1) {
+                s0 = f32x4{0.f, 0.f, 0.f, 0.f};
+                s1 = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < QREGS; ++kk) {
+                    s0 = mfma16<T>(kf[0][kk], qf[t][kk], s0);
+                    s1 = mfma16<T>(kf[1][kk], qf[t][kk], s1);
+                }
+            };
+            const uint4 ones = make_uint4(ones2<T>(), ones2<T>(), ones2<T>(), ones2<T>());
+
+            uint4 kfA[2][QREGS], kfB[2][QREGS], vf[NT];
+            uint32_t vraw[8][NT / 2];
+            f32x4 sn0, sn1;
+            uint4 pprev = make_uint4(0, 0, 0, 0);
+
+            // prologue: one more stage in flight than the plain loop keeps, the
+            // first step's fragments, the frozen reference, S of the first slot
+            if (issued < nstages) {
+                issue_stage(issued);
+                ++issued;
+            }
+            wait_stage(0);
+            __syncthreads();
+            load_k(step_base(0), kfA);
+            load_vraw(step_base(0) + STAGE, vraw);
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) {
+                scores(kfA, t, sn0, sn1);
+                const float tm = fmaxf(fmaxf(fmaxf(sn0[0], sn0[1]), fmaxf(sn0[2], sn0[3])),
+                                       fmaxf(fmaxf(sn1[0], sn1[1]), fmaxf(sn1[2], sn1[3])));
+                m[t] = quad_column_max(tm) * p.c_log2;
+            }
+            scores(kfA, 0, sn0, sn1);
+            make_vf(vraw, vf);       // placeholder operand for the first (all-zero P) slot
+
+            auto do_step = [&](int jj, uint4 (&kf_cur)[2][QREGS], uint4 (&kf_nxt)[2][QREGS]) {
+                const int jn = min(jj + 1, J - 1);
+                const int s_cur = (WK == 2) ? jj : (jj >> 1), s_nxt = (WK == 2) ? jn : (jn >> 1);
+                if (s_nxt != s_cur) {                            // uniform over the workgroup
+                    __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0): my LDS reads are done
+                    wait_stage(s_nxt);
+                    __syncthreads();
+                    if (issued < nstages) {
+                        issue_stage(issued);                     // into the slot of stage s_cur
+                        ++issued;
+                    }
+                }
+                const unsigned char *Kn = step_base(jn);
+#pragma unroll
+                for (int t = 0; t < TPW; ++t) {
+                    const f32x4 c0 = sn0, c1 = sn1;
+                    constexpr int kNone = 0;
+                    (void)kNone;
+                    const int tp = (t + TPW - 1) % TPW;
+                    // MFMA: PV of the previous slot
+#pragma unroll
+                    for (int u = 0; u < NT; ++u) O[tp][u] = mfma16<T>(vf[u], pprev, O[tp][u]);
+                    O[tp][NT] = mfma16<T>(ones, pprev, O[tp][NT]);
+                    if (t == 0) make_vf(vraw, vf);               // this step's V^T fragments
+                    // MFMA: scores of the next slot
+                    if (t + 1 < TPW) scores(kf_cur, t + 1, sn0, sn1);
+                    else scores(kf_nxt, 0, sn0, sn1);
+                    // VALU: probabilities of this slot
+                    float e0[4], e1[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        e0[r] = fast_exp2(__builtin_fmaf(c0[r], p.c_log2, -m[t]));
+                        e1[r] = fast_exp2(__builtin_fmaf(c1[r], p.c_log2, -m[t]));
+                    }
+                    pprev.x = pack2<T>(e0[0], e0[1]);
+                    pprev.y = pack2<T>(e0[2], e0[3]);
+                    pprev.z = pack2<T>(e1[0], e1[1]);
+                    pprev.w = pack2<T>(e1[2], e1[3]);
+                    // LDS: fragments of the next step
+                    if (t == 0) {
+                        load_k(Kn, kf_nxt);
+                        load_vraw(Kn + STAGE, vraw);
+                    }
+                }
+            };
+            for (int jj = 0; jj < J; jj += 2) {
+                do_step(jj, kfA, kfB);
+                if (jj + 1 < J) do_step(jj + 1, kfB, kfA);
+            }
+            // drain: PV of the very last slot
+#pragma unroll
+            for (int u = 0; u < NT; ++u) O[TPW - 1][u] = mfma16<T>(vf[u], pprev, O[TPW - 1][u]);
+            O[TPW - 1][NT] = mfma16<T>(ones, pprev, O[TPW - 1][NT]);
         }
     };
 
@@ -501,10 +641,14 @@ __global__ void __launch_bounds__(256) splitkv_kernel(const KParams p)
         int n_fast = 0;
         if (kHasFast && pass == 0) n_fast = max(0, min(nstages, (L - pos0) / SK));
         if (n_fast > 0) {
-            wait_stage(0);
-            __syncthreads();
-            init_reference(0, wk);
-            run_stages(0, n_fast, std::true_type{});
+            if constexpr (TPW >= 2) {
+                run_fast_pipelined(n_fast);
+            } else {
+                wait_stage(0);
+                __syncthreads();
+                init_reference(0, wk);
+                run_stages(0, n_fast, std::true_type{});
+            }
         }
         run_stages(n_fast, nstages, std::false_type{});
         if (!kHasFast || pass == 1) break;
