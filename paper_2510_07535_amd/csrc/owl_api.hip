@@ -65,19 +65,18 @@ owl_status make_plan(const owl_verify_desc *d, FullPlan *fp)
     const int G = d->n_q_heads / d->n_kv_heads;
     const int R = G * d->n_draft;
     const int RT = (R + kRowTile - 1) / kRowTile;
+    // Eight wavefronts per workgroup: WR of them split the row tiles, WK the
+    // 32-key steps of a stage; a wave holds up to three tiles in accumulators.
     int tpw, wr, wk, rgs;
     if (d->qkv_dtype == OWL_F32) {
-        tpw = 1; wr = 4; wk = 1; rgs = (RT + 3) / 4;
-    } else if (RT <= 2) {
-        tpw = 1; wr = 2; wk = 2; rgs = 1;
+        tpw = 1; wr = 8; wk = 1; rgs = (RT + 7) / 8;
     } else if (RT <= 4) {
-        tpw = 2; wr = 2; wk = 2; rgs = 1;
+        tpw = 1; wr = 4; wk = 2; rgs = 1;
     } else {
-        wr = 4; wk = 1;
-        rgs = (RT + 19) / 20;
+        wr = 8; wk = 1;
+        rgs = (RT + 23) / 24;
         const int per_wg = (RT + rgs - 1) / rgs;
-        tpw = (per_wg + 3) / 4;
-        if (tpw < 2) tpw = 2;
+        tpw = (per_wg + 7) / 8;
     }
     const Variant *v = find_variant(d->qkv_dtype, d->head_dim, tpw, wr, wk);
     if (!v) return OWL_ERR_UNSUPPORTED;
@@ -92,9 +91,8 @@ owl_status make_plan(const owl_verify_desc *d, FullPlan *fp)
         // but splits long enough that the partials they write stay a small
         // fraction of the K/V bytes they read (ratio ~ 2R / C).
         const int64_t streams = (int64_t)d->batch * d->n_kv_heads * rgs;
-        const int occ = tpw <= 2 ? 2 : 1;
         const int rounds = streams >= 64 ? 4 : 1;
-        const int64_t want = (int64_t)device_cus() * occ * rounds;
+        const int64_t want = (int64_t)device_cus() * rounds;      // one workgroup per CU at a time
         int64_t S = (want + streams - 1) / streams;
         if (S < 1) S = 1;
         C = align_up((size_t)((T + S - 1) / S), kSplitQuantum);

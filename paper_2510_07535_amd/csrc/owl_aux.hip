@@ -10,9 +10,9 @@ namespace owl {
 // l_s = sum_k 2^(x_k - m_s) over the split's visible keys (x = score*log2 e;
 // m_s is the reference the split happened to use, not necessarily its max).
 // With M = max_s m_s:   out = sum_s 2^(m_s-M) O_s / sum_s 2^(m_s-M) l_s.
-// Partials are stored as raw accumulator fragments: float4 index
-// [slot][r][u][lane] holds channels 4*NT*quad + NT*r + 4*u .. +3 of row lane%16.
-// Wave r of the workgroup reduces register row r.
+// Partials are stored as raw accumulator fragments: float4 [slot][u][lane]
+// holds channels 16*u + 4*quad .. +3 of row lane%16.  Wave r of the workgroup
+// reduces the channel tiles u = r, r + 4, ...
 // ---------------------------------------------------------------------------
 template <int D>
 __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
@@ -40,7 +40,7 @@ __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
         const float4 *po = reinterpret_cast<const float4 *>(p.part_o) + slot * (size_t)(NT * 64) + lane;
 #pragma unroll
         for (int u = 0; u < NU; ++u) {
-            const float4 x = po[(r * NU + u) * 64];
+            const float4 x = po[(r + 4 * u) * 64];
             acc[u].x += w * x.x; acc[u].y += w * x.y; acc[u].z += w * x.z; acc[u].w += w * x.w;
         }
     }
@@ -48,10 +48,10 @@ __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
     if (row >= p.R) return;
     const int i = row / p.G, hh = row % p.G;
     const float inv = 1.0f / lsum;
-    float *o = p.out + (((int64_t)b * p.N + i) * p.Hq + g * p.G + hh) * D + 4 * NT * qd + NT * r;
+    float *o = p.out + (((int64_t)b * p.N + i) * p.Hq + g * p.G + hh) * D + 4 * qd;
 #pragma unroll
     for (int u = 0; u < NU; ++u)
-        *reinterpret_cast<float4 *>(o + 4 * u) =
+        *reinterpret_cast<float4 *>(o + 16 * (r + 4 * u)) =
             make_float4(acc[u].x * inv, acc[u].y * inv, acc[u].z * inv, acc[u].w * inv);
 }
 

@@ -42,7 +42,7 @@ def test_plan_matches_shapes():
     assert p.split_tokens % 128 == 0 and p.split_tokens * p.max_splits >= 32768 + 6
     assert p.workspace_bytes == B.owl_verify_attn_workspace_size(_good())
     p = B.owl_verify_attn_plan(_good(n_draft=40, n_q_heads=64, max_ctx_len=131072, max_pages_per_seq=8200))
-    assert p.rows_per_kv == 320 and p.row_tiles == 20 and p.tiles_per_wave == 5
+    assert p.rows_per_kv == 320 and p.row_tiles == 20 and p.tiles_per_wave == 3
     p = B.owl_verify_attn_plan(_good(split_tokens=1000))
     assert p.split_tokens == 1024
     p = B.owl_verify_attn_plan(_good(n_draft=64, n_q_heads=64))        # 512 rows
