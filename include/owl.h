@@ -217,6 +217,17 @@ owl_status owl_gather_read_probe(const void *src, const int32_t *block_order, in
  */
 owl_status owl_selftest_quad_max(const float *in64, float *out64, void *stream);
 
+/*
+ * Profiling aid.  With a non-NULL device buffer of 8 * n_workgroups int64,
+ * every workgroup of the split-KV pass of later owl_verify_attn calls records
+ * the GPU's constant-rate wall clock at: [0] entry, [1] page list and tree mask
+ * ready, [2] first stage in LDS, [3] end of the fast loop, [4] end of the
+ * careful loop, [5] partials written; [6] = its XCC id, [7] = its flat
+ * workgroup index.  NULL (the default) switches recording off.  Not
+ * thread-safe; meant for one measuring process.
+ */
+owl_status owl_debug_set_timeline(long long *buffer);
+
 /* Static string for a status code. */
 const char *owl_status_str(owl_status s);
 

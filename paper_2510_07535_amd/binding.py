@@ -22,7 +22,7 @@ OWL_DEV_BAD_PARENT, OWL_DEV_BAD_PAGE, OWL_DEV_BAD_CTX_LEN = 1, 2, 4
 EXPORTS = (
     "owl_verify_attn_plan", "owl_verify_attn_workspace_size", "owl_verify_attn",
     "owl_verify_attn_phases", "owl_stream_read_probe", "owl_selftest_quad_max",
-    "owl_gather_read_probe",
+    "owl_gather_read_probe", "owl_debug_set_timeline",
     "owl_build_tree_mask", "owl_build_tree_mask_host", "owl_gather_kv",
     "owl_status_str", "owl_version",
 )
@@ -90,6 +90,8 @@ def lib() -> ctypes.CDLL:
         l.owl_stream_read_probe.argtypes = [vp, ctypes.c_size_t, vp, i32, vp]
         l.owl_gather_read_probe.restype = ctypes.c_int
         l.owl_gather_read_probe.argtypes = [vp, vp, i32, vp, i32, vp]
+        l.owl_debug_set_timeline.restype = ctypes.c_int
+        l.owl_debug_set_timeline.argtypes = [vp]
         l.owl_selftest_quad_max.restype = ctypes.c_int
         l.owl_selftest_quad_max.argtypes = [vp, vp, vp]
         l.owl_build_tree_mask.restype = ctypes.c_int
@@ -183,6 +185,11 @@ def owl_gather_read_probe(src, block_order, sink, n_workgroups: int, stream: Opt
     rc = lib().owl_gather_read_probe(_ptr(src), _ptr(block_order), int(block_order.numel()), _ptr(sink),
                                      n_workgroups, _stream() if stream is None else stream)
     _check(rc, "owl_gather_read_probe")
+
+
+def owl_debug_set_timeline(buffer) -> None:
+    """buffer: int64 CUDA tensor with 8 entries per split-KV workgroup, or None to switch off."""
+    _check(lib().owl_debug_set_timeline(_ptr(buffer)), "owl_debug_set_timeline")
 
 
 def owl_selftest_quad_max(in64, out64, stream: Optional[int] = None) -> None:

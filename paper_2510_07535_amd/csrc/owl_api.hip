@@ -141,6 +141,8 @@ owl_status ensure_lds_attr(const Variant *v)
     return OWL_OK;
 }
 
+long long *g_timeline = nullptr;   // set by owl_debug_set_timeline
+
 bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
 
 }  // namespace
@@ -215,6 +217,7 @@ owl_status owl_verify_attn_phases(const owl_verify_desc *desc, const void *q, co
     p.stride_page = desc->kv_stride_page; p.stride_head = desc->kv_stride_head;
     p.stride_token = desc->kv_stride_token; p.n_pool_pages = desc->n_pool_pages;
     p.c_log2 = desc->scale * 1.4426950408889634f;
+    p.timeline = g_timeline;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     dim3 grid(p.max_splits, p.Hkv * p.row_groups, p.B);
@@ -288,6 +291,12 @@ owl_status owl_gather_read_probe(const void *src, const int32_t *block_order, in
     if (launch_gather_read(src, block_order, n_blocks, sink, n_workgroups,
                            static_cast<hipStream_t>(stream)) != hipSuccess)
         return OWL_ERR_HIP;
+    return OWL_OK;
+}
+
+owl_status owl_debug_set_timeline(long long *buffer)
+{
+    g_timeline = buffer;
     return OWL_OK;
 }
 

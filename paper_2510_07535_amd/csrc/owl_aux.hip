@@ -5,43 +5,76 @@
 namespace owl {
 
 // ---------------------------------------------------------------------------
-// Combine.  One workgroup per (sequence, KV head, 16-row tile).  A partial of
-// split s is the triple (m_s, l_s, O_s) with O_s = sum_k 2^(x_k - m_s) v_k and
-// l_s = sum_k 2^(x_k - m_s) over the split's visible keys (x = score*log2 e;
-// m_s is the reference the split happened to use, not necessarily its max).
-// With M = max_s m_s:   out = sum_s 2^(m_s-M) O_s / sum_s 2^(m_s-M) l_s.
+// Combine.  A partial of split s is the triple (m_s, l_s, O_s) with
+// O_s = sum_k 2^(x_k - m_s) v_k and l_s = sum_k 2^(x_k - m_s) over the split's
+// visible keys (x = score * log2 e; m_s is the reference the split happened to
+// use, not necessarily its max).  With M = max_s m_s:
+//     out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
 // Partials are stored as raw accumulator fragments: float4 [slot][u][lane]
-// holds channels 16*u + 4*quad .. +3 of row lane%16.  Wave r of the workgroup
-// reduces the channel tiles u = r, r + 4, ...
+// holds channels 16*u + 4*quad .. +3 of row lane%16.
+//
+// One workgroup per (sequence, KV head, 16-row tile, pair of channel tiles);
+// its four waves take every fourth split, reduce their share against their own
+// running maximum, and are merged through LDS with the same formula.
 // ---------------------------------------------------------------------------
 template <int D>
 __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
 {
-    constexpr int NT = D / 16, NU = NT / 4;
-    const int tg = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
-    const int lane = threadIdx.x & 63, r = threadIdx.x >> 6;
+    constexpr int NT = D / 16, UPW = 2;              // channel tiles per workgroup
+    constexpr int NUG = NT / UPW;
+    const int tg = blockIdx.x / NUG, u0 = (blockIdx.x % NUG) * UPW;
+    const int g = blockIdx.y, b = blockIdx.z;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int j = lane & 15, qd = lane >> 4;
 
     const int L = load_ctx_len(p.ctx_lens, b, p.max_ctx_len, nullptr);
     const int ns = (L + p.N + p.C - 1) / p.C;
     const size_t slot0 = (((size_t)b * p.Hkv + g) * p.max_splits) * p.RT + tg;
 
-    float M = -INFINITY;
-    for (int s = 0; s < ns; ++s) M = fmaxf(M, p.part_ml[(slot0 + (size_t)s * p.RT) * 32 + j]);
-
-    float4 acc[NU];
+    float mw = -INFINITY, lw = 0.f;
+    float4 acc[UPW];
 #pragma unroll
-    for (int u = 0; u < NU; ++u) acc[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-    float lsum = 0.f;
-    for (int s = 0; s < ns; ++s) {
+    for (int u = 0; u < UPW; ++u) acc[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s = w; s < ns; s += 4) {
         const size_t slot = slot0 + (size_t)s * p.RT;
-        const float w = __builtin_amdgcn_exp2f(p.part_ml[slot * 32 + j] - M);
-        lsum += w * p.part_ml[slot * 32 + 16 + j];
+        const float ms = p.part_ml[slot * 32 + j];
+        const float ls = p.part_ml[slot * 32 + 16 + j];
         const float4 *po = reinterpret_cast<const float4 *>(p.part_o) + slot * (size_t)(NT * 64) + lane;
+        float4 x[UPW];
 #pragma unroll
-        for (int u = 0; u < NU; ++u) {
-            const float4 x = po[(r + 4 * u) * 64];
-            acc[u].x += w * x.x; acc[u].y += w * x.y; acc[u].z += w * x.z; acc[u].w += w * x.w;
+        for (int u = 0; u < UPW; ++u) x[u] = po[(u0 + u) * 64];
+        const float mn = fmaxf(mw, ms);
+        const float a = __builtin_amdgcn_exp2f(mw - mn);     // 0 on the first round (mw = -inf)
+        const float c = __builtin_amdgcn_exp2f(ms - mn);
+        mw = mn;
+        lw = lw * a + ls * c;
+#pragma unroll
+        for (int u = 0; u < UPW; ++u) {
+            acc[u].x = acc[u].x * a + x[u].x * c; acc[u].y = acc[u].y * a + x[u].y * c;
+            acc[u].z = acc[u].z * a + x[u].z * c; acc[u].w = acc[u].w * a + x[u].w * c;
+        }
+    }
+    __shared__ float4 s_acc[4][UPW][64];
+    __shared__ float s_m[4][64], s_l[4][64];
+#pragma unroll
+    for (int u = 0; u < UPW; ++u) s_acc[w][u][lane] = acc[u];
+    s_m[w][lane] = mw;
+    s_l[w][lane] = lw;
+    __syncthreads();
+    if (w != 0) return;
+    float M = fmaxf(fmaxf(s_m[0][lane], s_m[1][lane]), fmaxf(s_m[2][lane], s_m[3][lane]));
+    float lsum = 0.f;
+    float4 tot[UPW];
+#pragma unroll
+    for (int u = 0; u < UPW; ++u) tot[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float wk = s_m[k][lane] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(s_m[k][lane] - M);
+        lsum += wk * s_l[k][lane];
+#pragma unroll
+        for (int u = 0; u < UPW; ++u) {
+            const float4 x = s_acc[k][u][lane];
+            tot[u].x += wk * x.x; tot[u].y += wk * x.y; tot[u].z += wk * x.z; tot[u].w += wk * x.w;
         }
     }
     const int row = tg * kRowTile + j;
@@ -50,14 +83,14 @@ __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
     const float inv = 1.0f / lsum;
     float *o = p.out + (((int64_t)b * p.N + i) * p.Hq + g * p.G + hh) * D + 4 * qd;
 #pragma unroll
-    for (int u = 0; u < NU; ++u)
-        *reinterpret_cast<float4 *>(o + 16 * (r + 4 * u)) =
-            make_float4(acc[u].x * inv, acc[u].y * inv, acc[u].z * inv, acc[u].w * inv);
+    for (int u = 0; u < UPW; ++u)
+        *reinterpret_cast<float4 *>(o + 16 * (u0 + u)) =
+            make_float4(tot[u].x * inv, tot[u].y * inv, tot[u].z * inv, tot[u].w * inv);
 }
 
 hipError_t launch_combine(const KParams &p, int D, hipStream_t s)
 {
-    dim3 grid(p.RT, p.Hkv, p.B);
+    dim3 grid(p.RT * (D / 32), p.Hkv, p.B);
     if (D == 128)
         hipLaunchKernelGGL(combine_kernel<128>, grid, dim3(256), 0, s, p);
     else

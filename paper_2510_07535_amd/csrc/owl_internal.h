@@ -31,6 +31,7 @@ struct KParams {
     int32_t row_groups;
     int64_t stride_page, stride_head, stride_token, n_pool_pages;
     float c_log2;         // scale * log2(e): scores live in the exp2 domain
+    long long *timeline;  // optional: 8 timestamps per workgroup (profiling aid), else null
 };
 
 // One instantiated split-KV kernel.

@@ -170,27 +170,99 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     const int g = blockIdx.y / p.row_groups, rg = blockIdx.y % p.row_groups;
     const int b = blockIdx.z;
 
+    // optional timeline of this workgroup (profiling aid)
+    long long *tl = nullptr;
+    if (p.timeline) {
+        const long long flat = blockIdx.x + (long long)gridDim.x * (blockIdx.y + (long long)gridDim.y * blockIdx.z);
+        tl = p.timeline + 8 * flat;
+        if (tid == 0) {
+            tl[0] = wall_clock64();
+            tl[1] = tl[2] = tl[3] = tl[4] = tl[5] = 0;
+            tl[6] = __smid();
+            tl[7] = flat;
+        }
+    }
+    auto stamp = [&](int k) {
+        if (tl && tid == 0) tl[k] = wall_clock64();
+    };
+
+    // ---- everything that does not depend on the context length is requested
+    // first, so that all of the kernel's set-up reads are in flight together:
+    // raw page-table entries of this split's window, the parent array, Q ----
+    const int pos0 = c * p.C;
+    const int win_pages = p.C / kPage;               // pages a full split spans (<= kMaxPagesPerSplit)
+    int raw_page[kMaxPagesPerSplit / kThreads];
+#pragma unroll
+    for (int r = 0; r < kMaxPagesPerSplit / kThreads; ++r) {
+        const int idx = tid + r * kThreads, lp = pos0 / kPage + idx;
+        raw_page[r] = -1;
+        if (idx < win_pages) {
+            if (!p.page_table) raw_page[r] = lp;
+            else if (lp < p.max_pages) raw_page[r] = p.page_table[(int64_t)b * p.max_pages + lp];
+        }
+    }
+    if (tid < p.N) s_parent[tid] = p.parent[(int64_t)b * p.N + tid];
+    // ---- this wave's query rows: tiles wr, wr + WR, ... of the row group ----
+    uint4 qf[TPW][KQ];
+    float qs[TPW][kF32 ? QREGS : 1];
+    int irow[TPW];
+    int my_nt = 0;
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) {
+        const int tg = rg * (WR * TPW) + t * WR + wr;
+        const bool tile_ok = tg < p.RT;
+        my_nt += tile_ok ? 1 : 0;
+        const int row = tg * kRowTile + j;
+        const bool ok = tile_ok && row < p.R;
+        const int i = ok ? row / p.G : 0;
+        const int hh = ok ? row % p.G : 0;
+        irow[t] = ok ? i : -1;
+        const unsigned char *qp = static_cast<const unsigned char *>(p.q) +
+            ((((int64_t)b * p.N + i) * p.Hq + g * p.G + hh) * D) * ES;
+        if constexpr (kF32) {
+#pragma unroll
+            for (int kk = 0; kk < QREGS; ++kk)
+                qs[t][kk] = ok ? reinterpret_cast<const float *>(qp)[4 * kk + qd] : 0.f;
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < QREGS; ++kk)
+                qf[t][kk] = ok ? *reinterpret_cast<const uint4 *>(qp + (32 * kk + 8 * qd) * ES)
+                               : make_uint4(0, 0, 0, 0);
+        }
+    }
+    my_nt = __builtin_amdgcn_readfirstlane(my_nt);
+
+
     const int L = load_ctx_len(p.ctx_lens, b, p.max_ctx_len, p.dev_status);
     const int Ttot = L + p.N;
-    const int pos0 = c * p.C;
     if (pos0 >= Ttot) return;                       // this split does not exist for b
     const int pos1 = min(pos0 + p.C, Ttot);
     const int nstages = (pos1 - pos0 + SK - 1) / SK;
 
-    // ---- page list of this split, and the tree mask if drafts are in reach ----
+    // ---- page list of this split (validated now that its extent is known),
+    // and the tree mask if drafts are in reach ----
     {
         const int npg = (pos1 - pos0 + kPage - 1) / kPage;
-        for (int idx = tid; idx < npg; idx += kThreads)
-            s_pages[idx] = load_page(p.page_table, b, p.max_pages, p.n_pool_pages,
-                                     pos0 / kPage + idx, p.dev_status);
+#pragma unroll
+        for (int r = 0; r < kMaxPagesPerSplit / kThreads; ++r) {
+            const int idx = tid + r * kThreads;
+            if (idx < npg) {
+                int pg = raw_page[r];
+                if (pg < 0 || pg >= p.n_pool_pages) {    // also: logical page beyond the table
+                    flag_status(p.dev_status, OWL_DEV_BAD_PAGE);
+                    pg = 0;
+                }
+                s_pages[idx] = pg;
+            }
+        }
     }
     const bool has_drafts = pos1 > L;               // uniform over the workgroup
-    if (has_drafts) {
-        if (tid < p.N) s_parent[tid] = p.parent[(int64_t)b * p.N + tid];
-        __syncthreads();
-        if (tid < p.N) s_anc[tid] = ancestor_set(s_parent, tid, nullptr, p.dev_status);
-    }
     __syncthreads();
+    if (has_drafts) {
+        if (tid < p.N) s_anc[tid] = ancestor_set(s_parent, tid, nullptr, p.dev_status);
+        __syncthreads();
+    }
+    stamp(1);
 
     // ---- stage issue ----
     // Wave w brings one 16-token page of one tensor per stage: tensor w/4 (K, V),
@@ -224,36 +296,6 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
                   __builtin_amdgcn_readfirstlane(lds_dst + it * RPI * ROWB));
         }
     };
-
-    // ---- this wave's query rows: tiles wr, wr + WR, ... of the row group ----
-    uint4 qf[TPW][KQ];
-    float qs[TPW][kF32 ? QREGS : 1];
-    int irow[TPW];
-    int my_nt = 0;
-#pragma unroll
-    for (int t = 0; t < TPW; ++t) {
-        const int tg = rg * (WR * TPW) + t * WR + wr;
-        const bool tile_ok = tg < p.RT;
-        my_nt += tile_ok ? 1 : 0;
-        const int row = tg * kRowTile + j;
-        const bool ok = tile_ok && row < p.R;
-        const int i = ok ? row / p.G : 0;
-        const int hh = ok ? row % p.G : 0;
-        irow[t] = ok ? i : -1;
-        const unsigned char *qp = static_cast<const unsigned char *>(p.q) +
-            ((((int64_t)b * p.N + i) * p.Hq + g * p.G + hh) * D) * ES;
-        if constexpr (kF32) {
-#pragma unroll
-            for (int kk = 0; kk < QREGS; ++kk)
-                qs[t][kk] = ok ? reinterpret_cast<const float *>(qp)[4 * kk + qd] : 0.f;
-        } else {
-#pragma unroll
-            for (int kk = 0; kk < QREGS; ++kk)
-                qf[t][kk] = ok ? *reinterpret_cast<const uint4 *>(qp + (32 * kk + 8 * qd) * ES)
-                               : make_uint4(0, 0, 0, 0);
-        }
-    }
-    my_nt = __builtin_amdgcn_readfirstlane(my_nt);
 
     f32x4 O[TPW][NT + 1];
     float m[TPW];
@@ -298,14 +340,19 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     // p = 2^(x - m) is exact in relative terms whatever m is; with m frozen at
     // the first step's row maximum, p overflows only if a later score exceeds
     // it by more than ~100 (log2 units), which the row sum exposes afterwards.
-    auto fast_step = [&](int buf, int ks, auto ntag) {
+    // A step is cut in two: scores + softmax -> P (fast_sx), and O += V^T P with
+    // the V^T fragments already in registers (fast_pv), so that the stage loop
+    // can put a barrier between them.
+    auto fast_sx = [&](const unsigned char *Kb, uint4 (&pf)[TPW], uint4 (&vf)[NT], auto ntag) {
         constexpr int NA = decltype(ntag)::value;    // tiles this wave really owns
         if constexpr (!kF32 && NA > 0) {
-            const unsigned char *Kb = smem + buf * 2 * STAGE + ks * 32 * ROWB;
-            const unsigned char *Vb = Kb + STAGE;
             uint4 kf[2][KQ];
+#ifdef OWL_ABLATE_KLOAD
+#pragma unroll
+            for (int kk = 0; kk < KQ; ++kk) { kf[0][kk] = make_uint4(kk, lane, 3, (uint32_t)(size_t)Kb); kf[1][kk] = make_uint4(lane, kk, 1, 2); }
+#else
             load_k_frags(Kb, kf);
-            uint4 pf[NA];
+#endif
 #pragma unroll
             for (int t = 0; t < NA; ++t) {
                 f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
@@ -314,6 +361,12 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
                     s0 = mfma16<T>(kf[0][kk], qf[t][kk], s0);
                     s1 = mfma16<T>(kf[1][kk], qf[t][kk], s1);
                 }
+#ifdef OWL_ABLATE_SOFTMAX
+                pf[t].x = __builtin_bit_cast(uint32_t, s0[0]) & 0x3F803F80u;
+                pf[t].y = __builtin_bit_cast(uint32_t, s0[2]) & 0x3F803F80u;
+                pf[t].z = __builtin_bit_cast(uint32_t, s1[0]) & 0x3F803F80u;
+                pf[t].w = __builtin_bit_cast(uint32_t, s1[2]) & 0x3F803F80u;
+#else
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     s0[r] = fast_exp2(__builtin_fmaf(s0[r], p.c_log2, -m[t]));
@@ -323,13 +376,25 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
                 pf[t].y = pack2<T>(s0[2], s0[3]);
                 pf[t].z = pack2<T>(s1[0], s1[1]);
                 pf[t].w = pack2<T>(s1[2], s1[3]);
+#endif
             }
+#ifdef OWL_ABLATE_VLOAD
+#pragma unroll
+            for (int u = 0; u < NT; ++u) vf[u] = make_uint4(u + lane, 0x3F803F80u, u, lane);
+#else
+#pragma unroll
+            for (int u = 0; u < NT; ++u) vf[u] = load_v_frag(Kb + STAGE, u);
+#endif
+        }
+    };
+    auto fast_pv = [&](const uint4 (&pf)[TPW], const uint4 (&vf)[NT], auto ntag) {
+        constexpr int NA = decltype(ntag)::value;
+        if constexpr (!kF32 && NA > 0) {
             const uint4 ones = make_uint4(ones2<T>(), ones2<T>(), ones2<T>(), ones2<T>());
 #pragma unroll
             for (int u = 0; u < NT; ++u) {
-                const uint4 vf = load_v_frag(Vb, u);
 #pragma unroll
-                for (int t = 0; t < NA; ++t) O[t][u] = mfma16<T>(vf, pf[t], O[t][u]);
+                for (int t = 0; t < NA; ++t) O[t][u] = mfma16<T>(vf[u], pf[t], O[t][u]);
             }
 #pragma unroll
             for (int t = 0; t < NA; ++t) O[t][NT] = mfma16<T>(ones, pf[t], O[t][NT]);
@@ -474,8 +539,8 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
         else if (NS > 2 && ahead == 1) wait_vmcnt<(NS > 2 ? 1 : 0) * LPS>();
         else wait_vmcnt<0>();
     };
-    // fast_tag: std::true_type = fast step with ntag tiles, std::false_type = careful step
-    auto run_stages = [&](int s_begin, int s_end, auto fast_tag, auto ntag) {
+    // careful stages [s_begin, s_end)
+    auto run_careful = [&](int s_begin, int s_end) {
         for (int s = s_begin; s < s_end; ++s) {
             wait_stage(s);
             __syncthreads();     // everyone's part of stage s is in; stage s-1 is fully consumed
@@ -487,24 +552,66 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
 #pragma unroll
             for (int ks = 0; ks < KSTEPS; ++ks) {
                 if (ks % WK != wk) continue;
-                if constexpr (decltype(fast_tag)::value) {
-                    fast_step(s % NS, ks, ntag);
+                if (sbase + ks * 32 >= pos1) continue;       // uniform: nothing left in this step
+                careful_step(s % NS, ks, sbase + ks * 32);
+            }
+        }
+    };
+    // fast stages [0, n_fast); the caller has admitted stage 0.
+    // The two waves of a SIMD (w and w + 4) would run in lockstep if both took
+    // the per-stage barrier at the same place in their instruction stream, and
+    // their MFMA phases and their exp/convert phases would collide.  So waves
+    // 4..7 take it one PV block later than waves 0..3: they carry the last PV of
+    // a stage (its P and V^T fragments are in registers by then, so the stage's
+    // ring slot is free all the same) across the barrier.  After every barrier
+    // the two waves of a SIMD are then half a step apart, and one's matrix work
+    // overlaps the other's vector work.
+    auto run_fast_n = [&](int n_fast, auto ntag) {
+        if constexpr (!kF32) {
+            const bool late = wave >= kWaves / 2;
+            auto kptr = [&](int s, int ks) -> const unsigned char * {
+                return smem + (s % NS) * 2 * STAGE + ks * 32 * ROWB;
+            };
+            auto admit = [&](int s) {
+                wait_stage(s);
+                __syncthreads();     // stage s is in; all LDS reads of stage s-1 have completed
+                if (issued < nstages) {
+                    issue_stage(issued);
+                    ++issued;
+                }
+            };
+            uint4 pf[TPW], vf[NT];
+            for (int s = 0; s < n_fast; ++s) {
+                if constexpr (WK == 1) {
+                    if (s > 0) {
+                        if (!late) fast_pv(pf, vf, ntag);        // early waves finish stage s-1 first
+                        admit(s);
+                        if (late) fast_pv(pf, vf, ntag);         // late waves carry it over
+                    }
+                    fast_sx(kptr(s, 0), pf, vf, ntag);
+                    fast_pv(pf, vf, ntag);
+                    fast_sx(kptr(s, 1), pf, vf, ntag);
                 } else {
-                    if (sbase + ks * 32 >= pos1) continue;   // uniform: nothing left in this step
-                    careful_step(s % NS, ks, sbase + ks * 32);
+                    if (s > 0) {
+                        if (!late) fast_pv(pf, vf, ntag);
+                        admit(s);
+                        if (late) fast_pv(pf, vf, ntag);
+                    }
+                    fast_sx(kptr(s, wk), pf, vf, ntag);
                 }
             }
+            fast_pv(pf, vf, ntag);
         }
     };
     // the fast loop is compiled once per possible tile count of a wave, so that
     // its body has no per-tile branches
-    auto run_fast = [&](int s_begin, int s_end) {
-        if (my_nt == TPW) run_stages(s_begin, s_end, std::true_type{}, std::integral_constant<int, TPW>{});
+    auto run_fast = [&](int n_fast) {
+        if (my_nt == TPW) run_fast_n(n_fast, std::integral_constant<int, TPW>{});
         else if (TPW > 1 && my_nt == TPW - 1)
-            run_stages(s_begin, s_end, std::true_type{}, std::integral_constant<int, (TPW > 1 ? TPW - 1 : 0)>{});
+            run_fast_n(n_fast, std::integral_constant<int, (TPW > 1 ? TPW - 1 : 0)>{});
         else if (TPW > 2 && my_nt == TPW - 2)
-            run_stages(s_begin, s_end, std::true_type{}, std::integral_constant<int, (TPW > 2 ? TPW - 2 : 0)>{});
-        else run_stages(s_begin, s_end, std::true_type{}, std::integral_constant<int, 0>{});
+            run_fast_n(n_fast, std::integral_constant<int, (TPW > 2 ? TPW - 2 : 0)>{});
+        else run_fast_n(n_fast, std::integral_constant<int, 0>{});
     };
     static_assert(TPW <= 3, "run_fast dispatches on at most three tile counts");
 
@@ -526,10 +633,17 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
         if (n_fast > 0) {
             wait_stage(0);
             __syncthreads();
+            stamp(2);
+            if (issued < nstages) {                 // the slot beyond the prologue's stages is free
+                issue_stage(issued);
+                ++issued;
+            }
             init_reference(0, wk);
-            run_fast(0, n_fast);
+            run_fast(n_fast);
         }
-        run_stages(n_fast, nstages, std::false_type{}, std::integral_constant<int, 0>{});
+        stamp(3);
+        run_careful(n_fast, nstages);
+        stamp(4);
         if (!kHasFast || pass == 1) break;
         bool bad = false;
 #pragma unroll
@@ -596,6 +710,10 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
                 p.part_ml[slot * 32 + 16 + j] = O[t][NT][0];
             }
         }
+    }
+    if (tl) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): the partial stores have left
+        stamp(5);
     }
 }
 
