@@ -30,6 +30,17 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MIN_ROTATION_BYTES = 2 << 30
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+
+
+def measured_traffic(workload):
+    """HBM bytes per split-KV launch from the committed rocprofv3 counter runs
+    (FETCH_SIZE + WRITE_SIZE, calibrated), or None if none was recorded."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            return json.load(f)["splitkv_kernel"][workload]["hbm_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def parse():
@@ -189,7 +200,7 @@ def main():
                    "page_size": 16, "kv_bytes_per_step": kbytes, "kv_copies_rotated": main_res["kv_copies_rotated"],
                    "plan": main_res["plan"]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(main_res["workload"]),
                      "kernel": "splitkv_kernel", "kernel_avg_us": main_res["split_kernel_avg_s"] * 1e6,
                      "kernel_median_us": main_res["split_kernel_median_s"] * 1e6,
                      "algorithmic_bytes_per_launch": kbytes},

@@ -347,12 +347,7 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
         constexpr int NA = decltype(ntag)::value;    // tiles this wave really owns
         if constexpr (!kF32 && NA > 0) {
             uint4 kf[2][KQ];
-#ifdef OWL_ABLATE_KLOAD
-#pragma unroll
-            for (int kk = 0; kk < KQ; ++kk) { kf[0][kk] = make_uint4(kk, lane, 3, (uint32_t)(size_t)Kb); kf[1][kk] = make_uint4(lane, kk, 1, 2); }
-#else
             load_k_frags(Kb, kf);
-#endif
 #pragma unroll
             for (int t = 0; t < NA; ++t) {
                 f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
@@ -361,12 +356,6 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
                     s0 = mfma16<T>(kf[0][kk], qf[t][kk], s0);
                     s1 = mfma16<T>(kf[1][kk], qf[t][kk], s1);
                 }
-#ifdef OWL_ABLATE_SOFTMAX
-                pf[t].x = __builtin_bit_cast(uint32_t, s0[0]) & 0x3F803F80u;
-                pf[t].y = __builtin_bit_cast(uint32_t, s0[2]) & 0x3F803F80u;
-                pf[t].z = __builtin_bit_cast(uint32_t, s1[0]) & 0x3F803F80u;
-                pf[t].w = __builtin_bit_cast(uint32_t, s1[2]) & 0x3F803F80u;
-#else
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     s0[r] = fast_exp2(__builtin_fmaf(s0[r], p.c_log2, -m[t]));
@@ -376,15 +365,9 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
                 pf[t].y = pack2<T>(s0[2], s0[3]);
                 pf[t].z = pack2<T>(s1[0], s1[1]);
                 pf[t].w = pack2<T>(s1[2], s1[3]);
-#endif
             }
-#ifdef OWL_ABLATE_VLOAD
-#pragma unroll
-            for (int u = 0; u < NT; ++u) vf[u] = make_uint4(u + lane, 0x3F803F80u, u, lane);
-#else
 #pragma unroll
             for (int u = 0; u < NT; ++u) vf[u] = load_v_frag(Kb + STAGE, u);
-#endif
         }
     };
     auto fast_pv = [&](const uint4 (&pf)[TPW], const uint4 (&vf)[NT], auto ntag) {
@@ -640,6 +623,8 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
             }
             init_reference(0, wk);
             run_fast(n_fast);
+        } else {
+            stamp(2);
         }
         stamp(3);
         run_careful(n_fast, nstages);

@@ -238,6 +238,43 @@ def test_gather_bit_exact(oracle_mod):
         assert step.dev_status() == 0
 
 
+def test_measurement_aids():
+    """The streaming probes read what they claim to (their XOR folds agree with
+    numpy) and the timeline hook records ordered timestamps for every workgroup."""
+    r = _rng(78)
+    host = r.integers(0, 2**31 - 1, size=(64 * 1024,), dtype=np.int64).astype(np.uint32)   # 256 KiB = 64 blocks
+    dev = torch.from_numpy(host.view(np.int32)).cuda()
+    want = int(np.bitwise_xor.reduce(host))
+    sink = torch.zeros(64, dtype=torch.int32, device="cuda")
+    B.owl_stream_read_probe(dev, sink, 8)
+    torch.cuda.synchronize()
+    assert int(np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32)[:8])) == want
+    order = torch.from_numpy(r.permutation(64).astype(np.int32)).cuda()
+    sink.zero_()
+    B.owl_gather_read_probe(dev, order, sink, 5)
+    torch.cuda.synchronize()
+    assert int(np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32)[:5])) == want
+
+    case = W.make_case("tl", 79, dtype=W.DT_BF16, Hq=32, Hkv=8, D=128, ctx_lens=[3000], trees=[W.random_tree(20, 4, r)])
+    step = VerifyStep(case, split_tokens=512)
+    step.run()
+    ref = step.result().copy()
+    nwg = step.plan.n_workgroups
+    tl = torch.zeros(8 * nwg, dtype=torch.int64, device="cuda")
+    B.owl_debug_set_timeline(tl)
+    try:
+        step.run()
+        got = step.result()
+    finally:
+        B.owl_debug_set_timeline(None)
+    assert np.array_equal(got, ref)                      # recording does not change the result
+    t = tl.cpu().numpy().reshape(nwg, 8)
+    ran = t[t[:, 0] > 0]
+    assert len(ran) == 8 * ((3000 + 20 + 511) // 512)    # one workgroup per (kv head, split)
+    assert (np.diff(ran[:, :6], axis=1) >= 0).all()
+    assert sorted(ran[:, 7]) == sorted(set(ran[:, 7]))
+
+
 # ---------------------------------------------------------------------------
 # data errors on the device are flagged, never followed out of bounds
 # ---------------------------------------------------------------------------
