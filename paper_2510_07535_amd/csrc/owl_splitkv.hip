@@ -90,6 +90,15 @@ __device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_addr)
                  : "memory", "m0");
 }
 
+// The same with a wave-uniform 64-bit base and a 32-bit per-lane byte offset.
+__device__ __forceinline__ void dma16s(uint64_t sbase, uint32_t voff, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(sbase)
+                 : "memory", "m0");
+}
+
 // Wait until at most N of this wavefront's vector-memory loads are in flight.
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
@@ -120,6 +129,16 @@ __device__ __forceinline__ float quad_column_max(float v)
     return fmaxf(__builtin_bit_cast(float, (uint32_t)r2[0]), __builtin_bit_cast(float, (uint32_t)r2[1]));
 }
 
+// f(integral_constant<int, B>) ... f(integral_constant<int, E-1>), unrolled at compile time.
+template <int B, int E, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        static_for<B + 1, E>(f);
+    }
+}
+
 // Geometry of one instantiation.
 template <typename T, int D, int TPW, int WR, int WK>
 struct Geo {
@@ -134,6 +153,7 @@ struct Geo {
     static constexpr int NT = D / 16;                   // channel tiles of O^T
     static constexpr int STAGE = SK * ROWB;             // bytes per tensor per stage
     static constexpr int NS = (8 * STAGE <= 131072) ? 4 : ((6 * STAGE <= 131072) ? 3 : 2);
+    static constexpr int VREG = NS * STAGE;             // LDS ring: K stages at [0, VREG), V stages behind them
     static constexpr int QREGS = kF32 ? D / 4 : D / 32; // Q fragment slots per tile
     static constexpr int KSWZ = (PPR - 1) & 15;         // K rows: piece ^= key & KSWZ
     static constexpr int VSWM = PPR >= 16 ? 7 : PPR / 2 - 1;   // V rows: piece ^= (key & VSWM) << 1
@@ -152,7 +172,7 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     constexpr int ES = GEO::ES, KSTEPS = GEO::KSTEPS, SK = GEO::SK, ROWB = GEO::ROWB;
     constexpr int PPR = GEO::PPR, NT = GEO::NT, STAGE = GEO::STAGE, NS = GEO::NS;
     constexpr int RPI = GEO::RPI, LPS = GEO::LPS, QREGS = GEO::QREGS;
-    constexpr int KSWZ = GEO::KSWZ, VSWM = GEO::VSWM;
+    constexpr int KSWZ = GEO::KSWZ, VSWM = GEO::VSWM, VREG = GEO::VREG;
     constexpr int KQ = kF32 ? 1 : QREGS;             // K/Q fragment slots of the 16-bit paths
 
     extern __shared__ __align__(16) unsigned char smem[];
@@ -280,13 +300,41 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     const int64_t head_off = (int64_t)g * p.stride_head * ES;
     const int64_t tok_bytes = p.stride_token * ES;
 
-    auto issue_stage = [&](int s) {
+    // A whole page (every stage but the split's last page) needs no clamping:
+    // the lane's byte offsets inside the page are fixed, only the page base
+    // (wave-uniform, kept in scalar registers) changes from stage to stage.
+    constexpr bool kKeepLdOff = TPW <= 2;            // three tiles per wave: no registers to spare, recompute
+    auto ld_off_of = [&](int it) -> uint32_t {
+        const int row = it * RPI + ld_row;
+        const int swz = ld_tensor ? ((row & VSWM) << 1) : (row & KSWZ);
+        return (uint32_t)(row * tok_bytes) + (uint32_t)((ld_piece ^ swz) << 4);
+    };
+    uint32_t ld_off[LPS];
+#pragma unroll
+    for (int it = 0; it < LPS; ++it) ld_off[it] = kKeepLdOff ? ld_off_of(it) : 0u;
+    const bool ld_off_ok = tok_bytes * kPage < ((int64_t)1 << 31);
+    const uint32_t ld_lds = lds0 + ld_tensor * VREG + ld_page * kPage * ROWB;
+
+    // page id of this wave's page of stage s (to be handed to issue_stage; reading it
+    // ahead of the stage barrier takes the LDS round trip off the issue path)
+    auto stage_page = [&](int s) -> int { return s_pages[min(s * (SK / kPage) + ld_page, last_pgx)]; };
+    auto issue_stage_pg = [&](int s, int pg_lane) {
         const int buf = s % NS;
         const int pgx_raw = s * (SK / kPage) + ld_page;
-        const int pgx = min(pgx_raw, last_pgx);
+        const uint32_t lds_dst = ld_lds + buf * STAGE;
+        if (pgx_raw < last_pgx && ld_off_ok) {           // uniform over the wave
+            const int64_t pg = __builtin_amdgcn_readfirstlane(pg_lane);
+            const uint64_t sb = (uint64_t)(uintptr_t)ld_base + (uint64_t)(pg * p.stride_page * ES + head_off);
+            const uint64_t sbase = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(sb >> 32)) << 32) |
+                                   (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)sb);
+#pragma unroll
+            for (int it = 0; it < LPS; ++it)
+                dma16s(sbase, kKeepLdOff ? ld_off[it] : ld_off_of(it),
+                       __builtin_amdgcn_readfirstlane(lds_dst + it * RPI * ROWB));
+            return;
+        }
         const int slot_max = pgx_raw >= last_pgx ? last_slot : kPage - 1;
-        const int64_t base = (int64_t)s_pages[pgx] * p.stride_page * ES + head_off;
-        const uint32_t lds_dst = lds0 + buf * 2 * STAGE + ld_tensor * STAGE + ld_page * kPage * ROWB;
+        const int64_t base = (int64_t)pg_lane * p.stride_page * ES + head_off;
 #pragma unroll
         for (int it = 0; it < LPS; ++it) {
             const int row = it * RPI + ld_row;
@@ -296,6 +344,7 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
                   __builtin_amdgcn_readfirstlane(lds_dst + it * RPI * ROWB));
         }
     };
+    auto issue_stage = [&](int s) { issue_stage_pg(s, stage_page(s)); };
 
     f32x4 O[TPW][NT + 1];
     float m[TPW];
@@ -343,7 +392,8 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     // A step is cut in two: scores + softmax -> P (fast_sx), and O += V^T P with
     // the V^T fragments already in registers (fast_pv), so that the stage loop
     // can put a barrier between them.
-    auto fast_sx = [&](const unsigned char *Kb, uint4 (&pf)[TPW], uint4 (&vf)[NT], auto ntag) {
+    auto fast_sx = [&](const unsigned char *Kb, const unsigned char *Vb, uint4 (&pf)[TPW], uint4 (&vf)[NT],
+                       auto ntag) {
         constexpr int NA = decltype(ntag)::value;    // tiles this wave really owns
         if constexpr (!kF32 && NA > 0) {
             uint4 kf[2][KQ];
@@ -367,7 +417,7 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
                 pf[t].w = pack2<T>(s1[2], s1[3]);
             }
 #pragma unroll
-            for (int u = 0; u < NT; ++u) vf[u] = load_v_frag(Kb + STAGE, u);
+            for (int u = 0; u < NT; ++u) vf[u] = load_v_frag(Vb, u);
         }
     };
     auto fast_pv = [&](const uint4 (&pf)[TPW], const uint4 (&vf)[NT], auto ntag) {
@@ -384,10 +434,114 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
         }
     };
 
+    // ---- pipelined fast loop (WK == 1, up to two tiles per wave) ----
+    // Iteration i runs three mutually independent instruction streams over
+    // 32-key steps: the matrix stream does O += V^T P of step i-1 and the
+    // scores of step i+1, the vector stream turns the scores of step i into P
+    // (fma, exp2, pack), and the LDS stream fetches each K / V^T fragment PF
+    // MFMA groups before its use (one group = one fragment's MFMAs for all tiles
+    // of the wave).  The streams are woven together group by group, with a
+    // scheduling fence after every group so that the order written here is the
+    // order issued: a wave can issue only one instruction every few cycles, so
+    // what keeps the matrix pipe busy is a short, evenly mixed stream per wave.
+    // Ring offsets are compile-time (the stage loop is unrolled over the ring)
+    // and travel in the LDS instructions' offset fields: no address arithmetic
+    // is left in the loop.
+    constexpr bool kPipe = !kF32 && WK == 1 && TPW <= 2;      // three tiles: not enough registers
+    constexpr int PF = 3;                                      // fragment prefetch distance (groups, <= NT)
+    uint32_t k_off[KQ], v_off[NT];
+    if constexpr (kPipe) {
+#pragma unroll
+        for (int kk = 0; kk < KQ; ++kk) k_off[kk] = j * ROWB + (((4 * kk + qd) ^ (j & KSWZ)) << 4);
+#pragma unroll
+        for (int u = 0; u < NT; ++u) v_off[u] = VREG + v_lane_off + ((((2 * u) ^ v_swz) | (v_c >> 1)) << 4);
+    }
+    // V^T fragment of channel tile u / K fragment (kt, kk) at ring offset `off` (bytes, compile-time)
+    auto pipe_v = [&](auto off, auto uu) -> uint4 {
+        constexpr uint32_t C = decltype(off)::value;
+        const unsigned char *a = smem + v_off[decltype(uu)::value];
+        const uint2 lo = lds_read_tr16(a + C);
+        const uint2 hi = lds_read_tr16(a + (C + 16 * ROWB));
+        return make_uint4(lo.x, lo.y, hi.x, hi.y);
+    };
+    auto pipe_k = [&](auto off, auto ktt, auto kkk) -> uint4 {
+        constexpr uint32_t C = decltype(off)::value + decltype(ktt)::value * 16 * ROWB;
+        return *reinterpret_cast<const uint4 *>(smem + k_off[decltype(kkk)::value] + C);
+    };
+    // vprev / knext / vnext: ring offsets of V of step i-1, K of step i+1, V of step i
+    auto pipe_iter = [&](f32x4 (&Sc)[TPW][2], f32x4 (&Sn)[TPW][2], const uint4 (&Pp)[TPW], uint4 (&Pc)[TPW],
+                         uint4 (&vpre)[PF], auto vprev, auto knext, auto vnext, auto haspv, auto ntag) {
+        constexpr int NA = decltype(ntag)::value;
+        constexpr bool kPV = decltype(haspv)::value;
+        if constexpr (kPipe && NA > 0) {
+            constexpr int G = NT + 1 + 2 * KQ;           // MFMA groups: PV tiles, row sum, score fragments
+            constexpr int NV = NA * 8;                   // scores per lane
+            const uint4 ones = make_uint4(ones2<T>(), ones2<T>(), ones2<T>(), ones2<T>());
+            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+            uint4 fr[G];
+            if constexpr (kPV) static_for<0, PF>([&](auto uu) { fr[decltype(uu)::value] = vpre[decltype(uu)::value]; });
+            static_for<0, G>([&](auto nn) {
+                constexpr int n = decltype(nn)::value;
+                // LDS stream
+                constexpr int pn = n + PF;
+                if constexpr (pn < NT) {
+                    if constexpr (kPV) fr[pn] = pipe_v(vprev, std::integral_constant<int, pn>{});
+                } else if constexpr (pn > NT && pn < G) {
+                    fr[pn] = pipe_k(knext, std::integral_constant<int, (pn - NT - 1) & 1>{},
+                                    std::integral_constant<int, ((pn - NT - 1) >> 1)>{});
+                } else if constexpr (pn >= G) {
+                    vpre[pn - G] = pipe_v(vnext, std::integral_constant<int, pn - G>{});
+                }
+                if constexpr (!kPV && n == 0) {          // the first PF score fragments, not prefetched by anyone
+                    static_for<NT + 1, (NT + 1 + PF < G ? NT + 1 + PF : G)>([&](auto gg) {
+                        constexpr int g2 = decltype(gg)::value;
+                        fr[g2] = pipe_k(knext, std::integral_constant<int, (g2 - NT - 1) & 1>{},
+                                        std::integral_constant<int, ((g2 - NT - 1) >> 1)>{});
+                    });
+                }
+                // matrix stream
+                static_for<0, NA>([&](auto tt) {
+                    constexpr int t = decltype(tt)::value;
+                    if constexpr (n < NT) {
+                        if constexpr (kPV) O[t][n] = mfma16<T>(fr[n], Pp[t], O[t][n]);
+                    } else if constexpr (n == NT) {
+                        if constexpr (kPV) O[t][NT] = mfma16<T>(ones, Pp[t], O[t][NT]);
+                    } else {
+                        constexpr int kt = (n - NT - 1) & 1, kk = (n - NT - 1) >> 1;
+                        if constexpr (kk == 0) Sn[t][kt] = mfma16<T>(fr[n], qf[t][kk], zero);
+                        else Sn[t][kt] = mfma16<T>(fr[n], qf[t][kk], Sn[t][kt]);
+                    }
+                });
+                // vector stream: scores [done1, done2) in this group, packs of the scores of the group before
+                constexpr int done0 = n >= 2 ? ((n - 1) * NV / (G - 1) < NV ? (n - 1) * NV / (G - 1) : NV) : 0;
+                constexpr int done1 = n >= 1 ? (n * NV / (G - 1) < NV ? n * NV / (G - 1) : NV) : 0;
+                constexpr int done2 = (n + 1) * NV / (G - 1) < NV ? (n + 1) * NV / (G - 1) : NV;
+                static_for<done1, done2>([&](auto ii) {
+                    constexpr int idx = decltype(ii)::value;
+                    constexpr int t = idx >> 3, kt = (idx >> 2) & 1, r = idx & 3;
+                    float e = fast_exp2(__builtin_fmaf(Sc[t][kt][r], p.c_log2, -m[t]));
+                    asm volatile("" : "+v"(e));          // pins the computation of the value to this group
+                    Sc[t][kt][r] = e;
+                });
+                static_for<done0 / 2, done1 / 2>([&](auto cc) {
+                    constexpr int cidx = decltype(cc)::value;
+                    constexpr int t = cidx >> 2, kt = (cidx >> 1) & 1, h = cidx & 1;
+                    uint32_t w = pack2<T>(Sc[t][kt][2 * h], Sc[t][kt][2 * h + 1]);
+                    asm volatile("" : "+v"(w));
+                    if constexpr (kt == 0 && h == 0) Pc[t].x = w;
+                    else if constexpr (kt == 0) Pc[t].y = w;
+                    else if constexpr (h == 0) Pc[t].z = w;
+                    else Pc[t].w = w;
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        }
+    };
+
     // ---- reference m of every row tile from one unmasked step (before the fast loop) ----
-    auto init_reference = [&](int buf, int ks) {
+    auto init_reference = [&](int buf, int ks, f32x4 (&keep)[TPW][2]) {
         if constexpr (!kF32) {
-            const unsigned char *Kb = smem + buf * 2 * STAGE + ks * 32 * ROWB;
+            const unsigned char *Kb = smem + buf * STAGE + ks * 32 * ROWB;
             uint4 kf[2][KQ];
             load_k_frags(Kb, kf);
 #pragma unroll
@@ -398,6 +552,8 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
                     s0 = mfma16<T>(kf[0][kk], qf[t][kk], s0);
                     s1 = mfma16<T>(kf[1][kk], qf[t][kk], s1);
                 }
+                keep[t][0] = s0;
+                keep[t][1] = s1;
                 const float tm = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
                                        fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
                 m[t] = quad_column_max(tm) * p.c_log2;
@@ -439,8 +595,8 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
 
     // ---- careful step: any step, any type ----
     auto careful_step = [&](int buf, int ks, int step_pos) {
-        const unsigned char *Kb = smem + buf * 2 * STAGE + ks * 32 * ROWB;
-        const unsigned char *Vb = Kb + STAGE;
+        const unsigned char *Kb = smem + buf * STAGE + ks * 32 * ROWB;
+        const unsigned char *Vb = Kb + VREG;
         if constexpr (kF32) {
             // fp32 path: 16x16x4 MFMA, one channel (QK) / one key (PV) per quad and step
 #pragma unroll
@@ -553,7 +709,7 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
         if constexpr (!kF32) {
             const bool late = wave >= kWaves / 2;
             auto kptr = [&](int s, int ks) -> const unsigned char * {
-                return smem + (s % NS) * 2 * STAGE + ks * 32 * ROWB;
+                return smem + (s % NS) * STAGE + ks * 32 * ROWB;
             };
             auto admit = [&](int s) {
                 wait_stage(s);
@@ -571,30 +727,85 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
                         admit(s);
                         if (late) fast_pv(pf, vf, ntag);         // late waves carry it over
                     }
-                    fast_sx(kptr(s, 0), pf, vf, ntag);
+                    fast_sx(kptr(s, 0), kptr(s, 0) + VREG, pf, vf, ntag);
                     fast_pv(pf, vf, ntag);
-                    fast_sx(kptr(s, 1), pf, vf, ntag);
+                    fast_sx(kptr(s, 1), kptr(s, 1) + VREG, pf, vf, ntag);
                 } else {
                     if (s > 0) {
                         if (!late) fast_pv(pf, vf, ntag);
                         admit(s);
                         if (late) fast_pv(pf, vf, ntag);
                     }
-                    fast_sx(kptr(s, wk), pf, vf, ntag);
+                    fast_sx(kptr(s, wk), kptr(s, wk) + VREG, pf, vf, ntag);
                 }
             }
             fast_pv(pf, vf, ntag);
         }
     };
+    // Pipelined fast stages [0, n_fast); the caller has admitted stage 0 and Sa
+    // holds the scores of step 0.  V of a step is read one iteration after its
+    // K, so a ring slot is refilled one stage later than in the plain loop: at
+    // the barrier in front of step 2s+1 every wave is done with stage s-1.
+    auto run_pipe_n = [&](int n_fast, f32x4 (&Sa)[TPW][2], auto ntag) {
+        if constexpr (kPipe) {
+            constexpr int NA = decltype(ntag)::value;
+            using yes = std::true_type;
+            using no = std::false_type;
+            f32x4 Sb[TPW][2];
+            uint4 Pa[TPW], Pb[TPW], vpre[PF];
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) {
+                Pa[t] = Pb[t] = make_uint4(0, 0, 0, 0);
+                Sb[t][0] = Sb[t][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int u = 0; u < PF; ++u) vpre[u] = make_uint4(0, 0, 0, 0);
+            // step 0: P of step 0, scores of step 1; no V^T P yet
+            pipe_iter(Sa, Sb, Pb, Pa, vpre, std::integral_constant<uint32_t, 0>{},
+                      std::integral_constant<uint32_t, 32 * ROWB>{}, std::integral_constant<uint32_t, 0>{}, no{}, ntag);
+            for (int s4 = 0; s4 < n_fast; s4 += NS) {
+                static_for<0, NS>([&](auto bb) {
+                    constexpr uint32_t B = decltype(bb)::value, B1 = (B + 1) % NS;
+                    constexpr uint32_t cur0 = B * STAGE, cur1 = B * STAGE + 32 * ROWB;
+                    constexpr uint32_t nxt0 = B1 * STAGE, nxt1 = B1 * STAGE + 32 * ROWB;
+                    const int s = s4 + (int)B;
+                    if (s < n_fast) {                                   // uniform
+                        // stage s+1 in; every wave is done with stage s-1: refill its slot
+                        const int pg = stage_page(issued);
+                        wait_stage(s + 1);
+                        __syncthreads();
+                        if (issued < nstages && issued <= s + NS - 1) {
+                            issue_stage_pg(issued, pg);
+                            ++issued;
+                        }
+                        // step 2s+1: its P; O += V^T P of step 2s; scores of step 2s+2
+                        pipe_iter(Sb, Sa, Pa, Pb, vpre, std::integral_constant<uint32_t, cur0>{},
+                                  std::integral_constant<uint32_t, nxt0>{}, std::integral_constant<uint32_t, cur1>{},
+                                  yes{}, ntag);
+                        // step 2s+2: its P; O += V^T P of step 2s+1; scores of step 2s+3.  After the
+                        // last fast stage only the V^T P part counts: the P and the scores it
+                        // produces belong to steps the careful loop redoes, and are dropped.
+                        pipe_iter(Sa, Sb, Pb, Pa, vpre, std::integral_constant<uint32_t, cur1>{},
+                                  std::integral_constant<uint32_t, nxt1>{}, std::integral_constant<uint32_t, nxt0>{},
+                                  yes{}, ntag);
+                    }
+                });
+            }
+        }
+    };
     // the fast loop is compiled once per possible tile count of a wave, so that
     // its body has no per-tile branches
-    auto run_fast = [&](int n_fast) {
-        if (my_nt == TPW) run_fast_n(n_fast, std::integral_constant<int, TPW>{});
+    auto run_fast_tag = [&](int n_fast, f32x4 (&Sa)[TPW][2], auto ntag) {
+        if constexpr (kPipe) run_pipe_n(n_fast, Sa, ntag);
+        else run_fast_n(n_fast, ntag);
+    };
+    auto run_fast = [&](int n_fast, f32x4 (&Sa)[TPW][2]) {
+        if (my_nt == TPW) run_fast_tag(n_fast, Sa, std::integral_constant<int, TPW>{});
         else if (TPW > 1 && my_nt == TPW - 1)
-            run_fast_n(n_fast, std::integral_constant<int, (TPW > 1 ? TPW - 1 : 0)>{});
+            run_fast_tag(n_fast, Sa, std::integral_constant<int, (TPW > 1 ? TPW - 1 : 0)>{});
         else if (TPW > 2 && my_nt == TPW - 2)
-            run_fast_n(n_fast, std::integral_constant<int, (TPW > 2 ? TPW - 2 : 0)>{});
-        else run_fast_n(n_fast, std::integral_constant<int, 0>{});
+            run_fast_tag(n_fast, Sa, std::integral_constant<int, (TPW > 2 ? TPW - 2 : 0)>{});
+        else run_fast_tag(n_fast, Sa, std::integral_constant<int, 0>{});
     };
     static_assert(TPW <= 3, "run_fast dispatches on at most three tile counts");
 
@@ -621,8 +832,9 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
                 issue_stage(issued);
                 ++issued;
             }
-            init_reference(0, wk);
-            run_fast(n_fast);
+            f32x4 Sa[TPW][2];
+            init_reference(0, wk, Sa);
+            run_fast(n_fast, Sa);
         } else {
             stamp(2);
         }
