@@ -153,6 +153,57 @@ def cpu_baseline(case, budget_rows=None):
     }
 
 
+def bench_steps(reps=200):
+    """The steps around the attention (Prepare, greedy acceptance, KV commit) on
+    the batched configuration's shapes: microseconds per call, launches queued
+    back to back.  They are launch-bound integer / data-movement kernels."""
+    import numpy as np
+    import torch
+    from paper_2510_07535_amd import binding as B
+    from paper_2510_07535_amd import workloads as W
+    from paper_2510_07535_amd.runner import VerifyStep
+    dev = "cuda:0"
+    case = W.make_config(4, ctx_scale=0.05)
+    Bn, N = case.B, case.N
+    n = N // 2
+    rng = np.random.Generator(np.random.Philox(key=99))
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+    parent_n = i32(case.tree_parent[:, :n].clip(max=n - 1))
+    ctx = i32(case.ctx_lens)
+    p2 = torch.zeros((Bn, 2 * n), dtype=torch.int32, device=dev)
+    anc = torch.zeros((Bn, 2 * n), dtype=torch.int64, device=dev)
+    dep = torch.zeros_like(p2)
+    pos = torch.zeros_like(p2)
+    tok, tgt = i32(rng.integers(0, 3, (Bn, N))), i32(rng.integers(0, 3, (Bn, N)))
+    root = i32(rng.integers(0, 3, Bn))
+    par = i32(case.tree_parent)
+    acc = torch.zeros((Bn, N), dtype=torch.int32, device=dev)
+    na, bonus, last = (torch.zeros(Bn, dtype=torch.int32, device=dev) for _ in range(3))
+    step = VerifyStep(case)
+    new_ctx = torch.zeros(Bn, dtype=torch.int32, device=dev)
+
+    def timed(fn):
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps * 1e6
+
+    res = {"shapes": {"batch": Bn, "n_draft": N, "n_kv_heads": case.Hkv, "head_dim": case.D}}
+    res["prepare_us"] = timed(lambda: B.owl_prepare_spec_tree(parent_n, ctx, p2, anc, dep, pos))
+    res["accept_us"] = timed(lambda: B.owl_accept_greedy(tok, par, root, tgt, N, acc, na, bonus, last))
+    B.owl_accept_greedy(tok, par, root, tgt, N, acc, na, bonus, last)
+    torch.cuda.synchronize()
+    res["commit_us"] = timed(lambda: B.owl_commit_kv(step.desc, step.k, step.v, step.page_table, step.ctx_lens,
+                                                     acc, na, new_ctx, step.status))
+    res["commit_rows_moved"] = int(na.sum().item()) * case.Hkv * 2
+    res["commit_bytes"] = res["commit_rows_moved"] * case.D * 2 * 2
+    return res
+
+
 def bench_config(idx, args, want_detail):
     from paper_2510_07535_amd import workloads as W
     case = W.make_config(idx)
@@ -217,6 +268,7 @@ def main():
             _, rot, r = bench_config(idx, args, True)
             others.append(r)
         line["others"] = others
+        line["step_kernels"] = bench_steps()
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(case)
     else:

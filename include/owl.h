@@ -64,6 +64,7 @@ typedef enum owl_dtype {
 #define OWL_DEV_BAD_PARENT 1u   /* some parent[i] not in {-1} u [0, i)            */
 #define OWL_DEV_BAD_PAGE 2u     /* a needed page id not in [0, n_pool_pages)      */
 #define OWL_DEV_BAD_CTX_LEN 4u  /* some ctx_lens[b] not in [0, max_ctx_len]       */
+#define OWL_DEV_BAD_ACCEPT 8u   /* accepted[] not a strictly increasing list in [0, n_draft) */
 
 /*
  * Shape of one verify step.  Strides are in ELEMENTS of qkv_dtype.
@@ -172,6 +173,64 @@ owl_status owl_verify_attn_phases(const owl_verify_desc *desc, const void *q, co
 owl_status owl_build_tree_mask(const int32_t *tree_parent, int32_t batch, int32_t n_draft,
                                uint64_t *anc_mask, int32_t *depth, uint32_t *dev_status,
                                void *stream);
+
+/*
+ * Prepare (Algorithm 1; Sec. 3.2.2, "Decode Stage"): the verify input of a
+ * drafted tree of n nodes is the n nodes followed by one extra token per node,
+ * the extra token of node k (index n + k) being placed after k's root path, so
+ * that it sees exactly that path and itself.  For every sequence b and token
+ * i < 2n this writes
+ *     tree_parent2[b][i]  parent array of the 2n-token tree (parent of n + k is k),
+ *                         ready to be handed to owl_verify_attn with n_draft = 2n
+ *     anc_mask[b][i]      as owl_build_tree_mask
+ *     depth[b][i]         tokens on i's root path, root = 1 (may be NULL)
+ *     pos_ids[b][i]       ctx_lens[b] + depth - 1, the position id (may be NULL)
+ * tree_parent [B][n], ctx_lens [B] int32 device; outputs [B][2n] device.
+ * n <= 32 (OWL_ERR_TOO_MANY_DRAFT beyond).  A parent outside {-1} u [0, i) is
+ * treated as a root and flagged (OWL_DEV_BAD_PARENT).
+ */
+owl_status owl_prepare_spec_tree(const int32_t *tree_parent, const int32_t *ctx_lens, int32_t batch,
+                                 int32_t n_nodes, int32_t *tree_parent2, uint64_t *anc_mask,
+                                 int32_t *depth, int32_t *pos_ids, uint32_t *dev_status, void *stream);
+
+/*
+ * Greedy acceptance after the verify pass (Sec. 1 and Sec. 2: the target model
+ * checks all drafted tokens in parallel and keeps those that match its own
+ * output, which leaves the output unchanged).  A node agrees if its token equals
+ * the target's next token at its parent (target_root[b], the target's next token
+ * after the context, for a root); the accepted path is the longest root path all
+ * of whose nodes agree, the one ending in the smallest node index on ties.
+ *     tokens      [B][N] int32 device  drafted token of node i (nodes >= n_cand,
+ *                                      the extra tokens of Prepare, are never candidates)
+ *     target_next [B][N] int32 device  the target's next token after node i's path
+ *     accepted    [B][N] int32 device  out: path nodes from the root down, then -1
+ *     n_accept    [B]    int32 device  out: the acceptance length of this step
+ *     bonus       [B]    int32 device  out: the target's next token after the path
+ *     last        [B]    int32 device  out: last accepted node or -1; with a tree
+ *                                      from owl_prepare_spec_tree, row n + last of the
+ *                                      verify pass is the extra token that follows the path
+ * N <= 64, 0 <= n_cand <= N.  No host synchronisation.
+ */
+owl_status owl_accept_greedy(const int32_t *tokens, const int32_t *tree_parent, const int32_t *target_root,
+                             const int32_t *target_next, int32_t batch, int32_t n_draft, int32_t n_cand,
+                             int32_t *accepted, int32_t *n_accept, int32_t *bonus, int32_t *last,
+                             uint32_t *dev_status, void *stream);
+
+/*
+ * Commit of the accepted tokens (Algorithm 1: the accepted draft is appended to
+ * the context and the context length grows by its length): for every sequence
+ * b, KV head g and i < n_accept[b], the K and V rows at logical position
+ * ctx_lens[b] + accepted[b][i] move to ctx_lens[b] + i, in place, in the cache
+ * described by desc (same layout and paging as owl_verify_attn; desc->n_draft
+ * is the row length N of accepted[]).  All rows are read before any is written.
+ * new_ctx_lens[b] = ctx_lens[b] + n_accept[b]; it may be NULL but must not be
+ * ctx_lens itself.  accepted[b][0..n_accept) must be strictly increasing and in
+ * [0, N) (a root path is), else nothing moves for b and OWL_DEV_BAD_ACCEPT is set.
+ * The caches are written; everything else is read only.
+ */
+owl_status owl_commit_kv(const owl_verify_desc *desc, void *k_cache, void *v_cache, const int32_t *page_table,
+                         const int32_t *ctx_lens, const int32_t *accepted, const int32_t *n_accept,
+                         int32_t *new_ctx_lens, uint32_t *dev_status, void *stream);
 
 /* Host twin of owl_build_tree_mask for one tree; all pointers are HOST memory.
  * Validates the tree: OWL_ERR_BAD_TREE if some parent[i] is not in {-1} u [0,i). */

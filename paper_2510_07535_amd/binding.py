@@ -17,13 +17,14 @@ OWL_BF16, OWL_F32, OWL_F16 = 0, 1, 2
 OWL_OK = 0
 OWL_ERR_INVALID_ARG, OWL_ERR_BAD_TREE, OWL_ERR_TOO_MANY_DRAFT = -1, -2, -3
 OWL_ERR_UNSUPPORTED, OWL_ERR_WORKSPACE, OWL_ERR_HIP = -4, -5, -6
-OWL_DEV_BAD_PARENT, OWL_DEV_BAD_PAGE, OWL_DEV_BAD_CTX_LEN = 1, 2, 4
+OWL_DEV_BAD_PARENT, OWL_DEV_BAD_PAGE, OWL_DEV_BAD_CTX_LEN, OWL_DEV_BAD_ACCEPT = 1, 2, 4, 8
 
 EXPORTS = (
     "owl_verify_attn_plan", "owl_verify_attn_workspace_size", "owl_verify_attn",
     "owl_verify_attn_phases", "owl_stream_read_probe", "owl_selftest_quad_max",
     "owl_gather_read_probe", "owl_debug_set_timeline",
     "owl_build_tree_mask", "owl_build_tree_mask_host", "owl_gather_kv",
+    "owl_prepare_spec_tree", "owl_accept_greedy", "owl_commit_kv",
     "owl_status_str", "owl_version",
 )
 
@@ -100,6 +101,12 @@ def lib() -> ctypes.CDLL:
         l.owl_build_tree_mask_host.argtypes = [vp, i32, vp, vp]
         l.owl_gather_kv.restype = ctypes.c_int
         l.owl_gather_kv.argtypes = [ctypes.POINTER(VerifyDesc), vp, vp, i32, i64, i64, vp, vp, vp]
+        l.owl_prepare_spec_tree.restype = ctypes.c_int
+        l.owl_prepare_spec_tree.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]
+        l.owl_accept_greedy.restype = ctypes.c_int
+        l.owl_accept_greedy.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]
+        l.owl_commit_kv.restype = ctypes.c_int
+        l.owl_commit_kv.argtypes = [ctypes.POINTER(VerifyDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp]
         l.owl_status_str.restype = ctypes.c_char_p
         l.owl_status_str.argtypes = [ctypes.c_int]
         l.owl_version.restype = ctypes.c_char_p
@@ -223,3 +230,29 @@ def owl_gather_kv(desc: VerifyDesc, cache, page_table, seq: int, first_pos: int,
                              n_tokens, _ptr(dst), _ptr(dev_status),
                              _stream() if stream is None else stream)
     _check(rc, "owl_gather_kv")
+
+
+def owl_prepare_spec_tree(tree_parent, ctx_lens, tree_parent2, anc_mask, depth=None, pos_ids=None,
+                          dev_status=None, stream: Optional[int] = None) -> None:
+    B, n = tree_parent.shape
+    rc = lib().owl_prepare_spec_tree(_ptr(tree_parent), _ptr(ctx_lens), B, n, _ptr(tree_parent2),
+                                     _ptr(anc_mask), _ptr(depth), _ptr(pos_ids), _ptr(dev_status),
+                                     _stream() if stream is None else stream)
+    _check(rc, "owl_prepare_spec_tree")
+
+
+def owl_accept_greedy(tokens, tree_parent, target_root, target_next, n_cand: int, accepted, n_accept, bonus,
+                      last, dev_status=None, stream: Optional[int] = None) -> None:
+    B, N = tokens.shape
+    rc = lib().owl_accept_greedy(_ptr(tokens), _ptr(tree_parent), _ptr(target_root), _ptr(target_next), B, N,
+                                 n_cand, _ptr(accepted), _ptr(n_accept), _ptr(bonus), _ptr(last),
+                                 _ptr(dev_status), _stream() if stream is None else stream)
+    _check(rc, "owl_accept_greedy")
+
+
+def owl_commit_kv(desc: VerifyDesc, k_cache, v_cache, page_table, ctx_lens, accepted, n_accept,
+                  new_ctx_lens=None, dev_status=None, stream: Optional[int] = None) -> None:
+    rc = lib().owl_commit_kv(ctypes.byref(desc), _ptr(k_cache), _ptr(v_cache), _ptr(page_table),
+                             _ptr(ctx_lens), _ptr(accepted), _ptr(n_accept), _ptr(new_ctx_lens),
+                             _ptr(dev_status), _stream() if stream is None else stream)
+    _check(rc, "owl_commit_kv")

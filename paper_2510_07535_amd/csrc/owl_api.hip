@@ -242,6 +242,52 @@ owl_status owl_build_tree_mask(const int32_t *tree_parent, int32_t batch, int32_
     return OWL_OK;
 }
 
+owl_status owl_prepare_spec_tree(const int32_t *tree_parent, const int32_t *ctx_lens, int32_t batch,
+                                 int32_t n_nodes, int32_t *tree_parent2, uint64_t *anc_mask,
+                                 int32_t *depth, int32_t *pos_ids, uint32_t *dev_status, void *stream)
+{
+    if (!tree_parent || !ctx_lens || !tree_parent2 || !anc_mask || batch < 1 || n_nodes < 1)
+        return OWL_ERR_INVALID_ARG;
+    if (n_nodes > 32) return OWL_ERR_TOO_MANY_DRAFT;
+    if (launch_prepare(tree_parent, ctx_lens, batch, n_nodes, tree_parent2, anc_mask, depth, pos_ids,
+                       dev_status, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return OWL_ERR_HIP;
+    return OWL_OK;
+}
+
+owl_status owl_accept_greedy(const int32_t *tokens, const int32_t *tree_parent, const int32_t *target_root,
+                             const int32_t *target_next, int32_t batch, int32_t n_draft, int32_t n_cand,
+                             int32_t *accepted, int32_t *n_accept, int32_t *bonus, int32_t *last,
+                             uint32_t *dev_status, void *stream)
+{
+    if (!tokens || !tree_parent || !target_root || !target_next || !accepted || !n_accept || !bonus || !last)
+        return OWL_ERR_INVALID_ARG;
+    if (batch < 1 || n_draft < 1 || n_cand < 0 || n_cand > n_draft) return OWL_ERR_INVALID_ARG;
+    if (n_draft > 64) return OWL_ERR_TOO_MANY_DRAFT;
+    if (launch_accept(tokens, tree_parent, target_root, target_next, batch, n_draft, n_cand, accepted,
+                      n_accept, bonus, last, dev_status, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return OWL_ERR_HIP;
+    return OWL_OK;
+}
+
+owl_status owl_commit_kv(const owl_verify_desc *desc, void *k_cache, void *v_cache, const int32_t *page_table,
+                         const int32_t *ctx_lens, const int32_t *accepted, const int32_t *n_accept,
+                         int32_t *new_ctx_lens, uint32_t *dev_status, void *stream)
+{
+    owl_status st = check_desc(desc);
+    if (st != OWL_OK) return st;
+    if (!k_cache || !v_cache || !ctx_lens || !accepted || !n_accept) return OWL_ERR_INVALID_ARG;
+    if (new_ctx_lens == ctx_lens) return OWL_ERR_INVALID_ARG;
+    if (misaligned(k_cache, 16) || misaligned(v_cache, 16)) return OWL_ERR_INVALID_ARG;
+    if (page_table &&
+        (int64_t)desc->max_pages_per_seq * kPage < (int64_t)desc->max_ctx_len + desc->n_draft)
+        return OWL_ERR_INVALID_ARG;
+    if (launch_commit(*desc, k_cache, v_cache, page_table, ctx_lens, accepted, n_accept, new_ctx_lens,
+                      dev_status, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return OWL_ERR_HIP;
+    return OWL_OK;
+}
+
 owl_status owl_build_tree_mask_host(const int32_t *parent, int32_t n_draft, uint64_t *anc,
                                     int32_t *depth)
 {

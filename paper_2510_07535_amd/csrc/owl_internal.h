@@ -46,6 +46,14 @@ const Variant *find_variant(int dtype, int D, int tpw, int wr, int wk);
 int variant_index(const Variant *v);
 
 hipError_t launch_combine(const KParams &p, int D, hipStream_t s);
+hipError_t launch_prepare(const int32_t *parent, const int32_t *ctx_lens, int B, int n, int32_t *parent2,
+                          uint64_t *anc, int32_t *depth, int32_t *pos, uint32_t *status, hipStream_t s);
+hipError_t launch_accept(const int32_t *tokens, const int32_t *parent, const int32_t *target_root,
+                         const int32_t *target_next, int B, int N, int n_cand, int32_t *accepted,
+                         int32_t *n_accept, int32_t *bonus, int32_t *last, uint32_t *status, hipStream_t s);
+hipError_t launch_commit(const owl_verify_desc &d, void *k_cache, void *v_cache, const int32_t *page_table,
+                         const int32_t *ctx_lens, const int32_t *accepted, const int32_t *n_accept,
+                         int32_t *new_ctx_lens, uint32_t *status, hipStream_t s);
 hipError_t launch_tree_mask(const int32_t *parent, int B, int N, uint64_t *anc, int32_t *depth,
                             uint32_t *status, hipStream_t s);
 hipError_t launch_gather(const owl_verify_desc &d, const void *cache, const int32_t *page_table,

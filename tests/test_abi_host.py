@@ -114,3 +114,31 @@ def test_mask_host_twin():
     assert lib.owl_build_tree_mask(0x1000, 1, 65, 0x1000, None, None, None) == B.OWL_ERR_TOO_MANY_DRAFT
     assert lib.owl_gather_kv(ctypes.byref(_good()), None, None, 0, 0, 1, 0x1000, None, None) == B.OWL_ERR_INVALID_ARG
     assert "workspace" in B.status_str(B.OWL_ERR_WORKSPACE)
+
+
+def test_step_entry_points_reject_before_launch():
+    """Prepare / accept / commit: argument errors are host-side and launch nothing."""
+    lib = B.lib()
+    A = 0x10000
+    # prepare: (parent, ctx, B, n, parent2, anc, depth, pos, status, stream)
+    assert lib.owl_prepare_spec_tree(None, A, 1, 3, A, A, None, None, None, None) == B.OWL_ERR_INVALID_ARG
+    assert lib.owl_prepare_spec_tree(A, A, 1, 3, None, A, None, None, None, None) == B.OWL_ERR_INVALID_ARG
+    assert lib.owl_prepare_spec_tree(A, A, 0, 3, A, A, None, None, None, None) == B.OWL_ERR_INVALID_ARG
+    assert lib.owl_prepare_spec_tree(A, A, 1, 33, A, A, None, None, None, None) == B.OWL_ERR_TOO_MANY_DRAFT
+    # accept: (tokens, parent, root, next, B, N, n_cand, accepted, n_accept, bonus, last, status, stream)
+    ok = [A, A, A, A, 1, 8, 8, A, A, A, A, None, None]
+    for null_at in (0, 1, 2, 3, 7, 8, 9, 10):
+        a = list(ok); a[null_at] = None
+        assert lib.owl_accept_greedy(*a) == B.OWL_ERR_INVALID_ARG
+    a = list(ok); a[6] = 9
+    assert lib.owl_accept_greedy(*a) == B.OWL_ERR_INVALID_ARG          # more candidates than nodes
+    a = list(ok); a[5] = 65; a[6] = 65
+    assert lib.owl_accept_greedy(*a) == B.OWL_ERR_TOO_MANY_DRAFT
+    # commit: (desc, k, v, page_table, ctx, accepted, n_accept, new_ctx, status, stream)
+    d = _good()
+    assert lib.owl_commit_kv(ctypes.byref(d), None, A, A, A, A, A, None, None, None) == B.OWL_ERR_INVALID_ARG
+    assert lib.owl_commit_kv(ctypes.byref(d), A, A, A, A, A, A, A, None, None) == B.OWL_ERR_INVALID_ARG   # new_ctx aliases ctx
+    assert lib.owl_commit_kv(ctypes.byref(d), A + 2, A, A, A, A, A, None, None, None) == B.OWL_ERR_INVALID_ARG
+    assert lib.owl_commit_kv(None, A, A, A, A, A, A, None, None, None) == B.OWL_ERR_INVALID_ARG
+    short = _good(max_pages_per_seq=100)
+    assert lib.owl_commit_kv(ctypes.byref(short), A, A, A, A, A, A, None, None, None) == B.OWL_ERR_INVALID_ARG
