@@ -86,7 +86,7 @@ typedef struct owl_verify_desc {
     int32_t max_ctx_len;        /* upper bound of ctx_lens[]; sizes the split plan       */
     int32_t qkv_dtype;          /* owl_dtype of q, k_cache, v_cache                      */
     int32_t split_tokens;       /* 0 = let the library choose; else tokens per KV split  */
-                                /* (rounded up to a multiple of 128) -- testing / tuning  */
+                                /* (rounded up to a multiple of 64) -- testing / tuning   */
     float scale;                /* multiplies q.k before the softmax, e.g. 1/sqrt(D)     */
     int32_t reserved_;          /* set to 0                                              */
     int64_t kv_stride_page, kv_stride_head, kv_stride_token;

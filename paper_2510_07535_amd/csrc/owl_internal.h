@@ -13,7 +13,7 @@ constexpr int kPage = 16;                 // tokens per cache page
 constexpr int kRowTile = 16;              // query rows per MFMA tile
 constexpr int kMaxSplitTokens = 16384;    // bounds the per-workgroup page list in LDS
 constexpr int kMaxPagesPerSplit = kMaxSplitTokens / kPage;
-constexpr int kSplitQuantum = 128;        // split_tokens is a multiple of every stage size
+constexpr int kSplitQuantum = 64;         // split_tokens is a multiple of every stage size
 
 // Everything a kernel needs, passed by value.
 struct KParams {

@@ -39,7 +39,7 @@ def test_struct_layout_matches_header():
 def test_plan_matches_shapes():
     p = B.owl_verify_attn_plan(_good())
     assert p.rows_per_kv == 24 and p.row_tiles == 2 and p.row_groups == 1 and p.tiles_per_wave == 1
-    assert p.split_tokens % 128 == 0 and p.split_tokens * p.max_splits >= 32768 + 6
+    assert p.split_tokens % 64 == 0 and p.split_tokens * p.max_splits >= 32768 + 6
     assert p.workspace_bytes == B.owl_verify_attn_workspace_size(_good())
     p = B.owl_verify_attn_plan(_good(n_draft=40, n_q_heads=64, max_ctx_len=131072, max_pages_per_seq=8200))
     assert p.rows_per_kv == 320 and p.row_tiles == 20 and p.tiles_per_wave == 3

@@ -74,7 +74,7 @@ def _small_cases():
 @pytest.mark.parametrize("case", _small_cases(), ids=lambda c: c.name)
 def test_small_shapes_match_oracle(oracle_mod, case):
     want = oracle_mod.verify_attn_case(case)
-    for split in (0, 128, 512):
+    for split in (0, 64, 192, 512):
         got, step = _run(case, split_tokens=split)
         assert_close(got, want, case.dtype, f"{case.name} split={split} plan={step.plan.as_dict()}")
 
