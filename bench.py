@@ -52,6 +52,8 @@ def parse():
                     help="0-based index into the benchmark configurations (default 3: 128K-context hybrid verify)")
     ap.add_argument("--all", action="store_true", help="also time the other bf16 configurations (reported under 'others')")
     ap.add_argument("--split-tokens", type=int, default=0, help="override the library's split size (tuning)")
+    ap.add_argument("--dtype", choices=("bf16", "f16"), default="bf16",
+                    help="storage type of q/K/V (the configurations list bf16; f16 is the paper's type)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
     return ap.parse_args()
@@ -206,7 +208,7 @@ def bench_steps(reps=200):
 
 def bench_config(idx, args, want_detail):
     from paper_2510_07535_amd import workloads as W
-    case = W.make_config(idx)
+    case = W.make_config(idx, dtype={"bf16": W.DT_BF16, "f16": W.DT_F16}[args.dtype])
     rot = Rotating(case, split_tokens=args.split_tokens)
     sec = rot.time_steps(args.steps, args.warmup)
     res = {

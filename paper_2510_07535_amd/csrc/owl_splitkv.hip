@@ -556,7 +556,9 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
                 keep[t][1] = s1;
                 const float tm = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
                                        fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
-                m[t] = quad_column_max(tm) * p.c_log2;
+                // fp16 holds 2^(x - m) only up to 2^16: its reference sits a little above the
+                // first step's maximum, which trades low-end resolution for head room
+                m[t] = quad_column_max(tm) * p.c_log2 + (std::is_same<T, _Float16>::value ? 4.0f : 0.0f);
             }
         }
     };
@@ -816,9 +818,11 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     // Pass 0: stages that lie wholly inside the prefix run the fast step with a
     // frozen reference; the rest (drafts, ragged end) run the careful step.
     // Pass 1 happens only if a row sum of pass 0 is not a modest finite number:
-    // the whole split is redone with the careful step.  bf16 only: an fp16 P
-    // cannot hold 2^(x - m) for a stale m, fp32 is the small correctness shape.
-    constexpr bool kHasFast = std::is_same<T, __bf16>::value;
+    // the whole split is redone with the careful step.  bf16 shares fp32's
+    // exponent range, so that happens only for scores ~100 above the reference;
+    // an fp16 P overflows 12 above it (and the redo is then the price).  fp32 is
+    // the small correctness shape and has no fast loop.
+    constexpr bool kHasFast = !kF32;
     for (int pass = 0; pass < 2; ++pass) {
         issued = 0;
         for (; issued < NS - 1 && issued < nstages; ++issued) issue_stage(issued);

@@ -281,11 +281,20 @@ def config_ctx_lens(idx: int, seed: Optional[int] = None) -> np.ndarray:
     raise ValueError(idx)
 
 
-def make_config(idx: int, seed: Optional[int] = None, ctx_scale: float = 1.0) -> Case:
+def make_config(idx: int, seed: Optional[int] = None, ctx_scale: float = 1.0, dtype: Optional[int] = None) -> Case:
     """Configuration ``idx`` (0-based, in the order of the benchmark list).
     ``ctx_scale`` < 1 shrinks every context length by that factor (kept for
-    CPU-sized parity runs of the same structure); 1.0 is the named size."""
+    CPU-sized parity runs of the same structure); 1.0 is the named size.
+    ``dtype`` replaces the storage type of configurations 1..4 (bf16 as listed;
+    DT_F16 is the type the paper's runs used)."""
     seed = idx + 1 if seed is None else seed
+    if dtype is not None and idx > 0:
+        base = make_config(idx, seed, ctx_scale)
+        if dtype == base.dtype:
+            return base
+        return make_case(base.name + {DT_F16: "_f16", DT_F32: "_f32", DT_BF16: ""}[dtype], seed, dtype=dtype,
+                         Hq=base.Hq, Hkv=base.Hkv, D=base.D, ctx_lens=base.ctx_lens,
+                         trees=list(base.tree_parent), outlier_frac=0.05 if idx == 3 else 0.0)
     trng = np.random.Generator(np.random.Philox(key=seed ^ 0x7EE))
     ctx = np.maximum(1, (config_ctx_lens(idx, seed).astype(np.float64) * ctx_scale).astype(np.int64))
     name = CONFIG_NAMES[idx] + ("" if ctx_scale == 1.0 else f"@{ctx_scale:g}")

@@ -64,6 +64,11 @@ def _small_cases():
            trees=[np.array([-1, -1, 0, 1, 1, -1, 5, 2], np.int32)]),
         # fp16 storage (the paper's inference type)
         mk("f16_tree30", 114, dtype=W.DT_F16, Hq=16, Hkv=4, D=128, ctx_lens=[1100], trees=[W.spec_tree(W.random_tree(15, 4, r))]),
+        # fp16 (the paper's dtype) through the fast loop: long enough for many fast stages; with
+        # outlier keys the fp16 P overflows its stale reference and the split is redone
+        mk("f16_tree60_L5000", 117, dtype=W.DT_F16, Hq=8, Hkv=2, D=128, ctx_lens=[5000], trees=[W.random_tree(60, 6, r)]),
+        mk("f16_outliers_L3000", 118, dtype=W.DT_F16, Hq=16, Hkv=2, D=128, ctx_lens=[3000, 900],
+           trees=[W.hybrid_tree(32, 8, r) for _ in range(2)], outlier_frac=0.05),
         # fp32 storage, both head dims
         mk("f32_D64_tree10", 115, dtype=W.DT_F32, Hq=8, Hkv=2, D=64, ctx_lens=[700, 33], trees=[W.random_tree(10, 4, r) for _ in range(2)]),
         mk("f32_D128_chain5", 116, dtype=W.DT_F32, Hq=4, Hkv=2, D=128, ctx_lens=[390], trees=[W.chain_tree(5)]),
@@ -101,6 +106,18 @@ def test_configs_full_size_sampled_rows(oracle_mod, idx):
     got, step = _run(case)
     nrows = 96 if idx < 4 else 64
     rows = sample_rows(case, nrows, seed=idx, always=[(0, 0, 0), (case.B - 1, case.N - 1, case.Hq - 1)])
+    want = oracle_mod.verify_attn_case(case, rows=rows)
+    sub = np.stack([got[b, i, h] for b, i, h in rows])
+    assert_close(sub, want, case.dtype, f"{case.name} plan={step.plan.as_dict()}")
+    assert np.isfinite(got).all()
+
+
+@pytest.mark.parametrize("idx", [2, 3])
+def test_configs_full_size_fp16(oracle_mod, idx):
+    """The long-context configurations stored as fp16 (the paper's inference type), full size."""
+    case = W.make_config(idx, dtype=W.DT_F16)
+    got, step = _run(case)
+    rows = sample_rows(case, 64, seed=40 + idx, always=[(0, 0, 0), (0, case.N - 1, case.Hq - 1)])
     want = oracle_mod.verify_attn_case(case, rows=rows)
     sub = np.stack([got[b, i, h] for b, i, h in rows])
     assert_close(sub, want, case.dtype, f"{case.name} plan={step.plan.as_dict()}")
