@@ -11,10 +11,18 @@
 //
 // Data movement: K/V go from HBM straight into LDS with 128-bit
 // global_load_lds (no VGPR staging), one 16-token page of one tensor per
-// wavefront and stage, 64 tokens per stage, in a ring of up to 4 stages that is
-// kept full ahead of the compute; readiness is tracked with vmcnt and one
-// barrier per stage.  Two wavefronts per SIMD let the hardware overlap one
-// wave's MFMA with the other's exp/convert work.
+// wavefront and stage, 64 tokens per stage, in a ring of up to 4 stages (K
+// stages in the lower half of the ring, V stages behind them) that is kept
+// full ahead of the compute; readiness is tracked with vmcnt and one barrier
+// per stage.
+//
+// Three loops share the ring: the pipelined fast loop (unmasked steps, up to
+// two tiles per wave: matrix, vector and LDS work of neighbouring steps woven
+// into one instruction stream), the plain fast loop (three tiles per wave, and
+// the layout with two key groups: scores -> softmax -> V^T P per step, the two
+// waves of a SIMD overlapping each other), and the careful loop (masked or
+// ragged steps, exact online softmax; also the fallback when a frozen softmax
+// reference overflowed).
 //
 // Tile algebra (all MFMA tiles are 16x16, wave64):
 //   S^T[key][row] = K[key][:] . Q[row][:]        A = K fragment, B = Q fragment

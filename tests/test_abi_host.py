@@ -142,3 +142,13 @@ def test_step_entry_points_reject_before_launch():
     assert lib.owl_commit_kv(None, A, A, A, A, A, A, None, None, None) == B.OWL_ERR_INVALID_ARG
     short = _good(max_pages_per_seq=100)
     assert lib.owl_commit_kv(ctypes.byref(short), A, A, A, A, A, A, None, None, None) == B.OWL_ERR_INVALID_ARG
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; any other --gpus exits with a message and code 2, before touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
