@@ -155,3 +155,30 @@ def gather_kv(case, which: str, b: int, first_pos: int, n_tokens: int) -> np.nda
     if rc:
         raise OracleError(rc)
     return dst
+
+
+def verify_attn_ragged_case(case, n_draft_seq) -> np.ndarray:
+    """A batch whose sequences carry different numbers of drafted tokens
+    (Algorithm 1 of the paper mixes sequence and tree drafts): sequence b is
+    verified on its own with the first n_draft_seq[b] nodes of its tree, i.e.
+    the plain step with N = n_draft_seq[b]; output rows of absent nodes are
+    zero.  Returns [B, N, Hq, D] (fp64)."""
+    kw = case_kwargs(case)
+    B, N = np.asarray(kw["tree_parent"]).shape
+    out = np.zeros((B, N, kw["Hq"], kw["D"]), dtype=np.float64)
+    for b in range(B):
+        n = int(n_draft_seq[b])
+        if not 0 <= n <= N:
+            raise ValueError("n_draft_seq out of range")
+        if n == 0:
+            continue
+        sub = dict(kw)
+        sub["q"] = np.ascontiguousarray(np.asarray(kw["q"])[b:b + 1, :n])
+        sub["tree_parent"] = np.ascontiguousarray(np.asarray(kw["tree_parent"])[b:b + 1, :n])
+        sub["ctx_lens"] = np.asarray(kw["ctx_lens"])[b:b + 1]
+        if kw["page_table"] is not None:
+            sub["page_table"] = np.asarray(kw["page_table"])[b:b + 1]
+        elif B != 1:
+            raise ValueError("identity paging is defined for one sequence")
+        out[b, :n] = verify_attn(**sub)[0]
+    return out

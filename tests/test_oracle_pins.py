@@ -365,3 +365,46 @@ def test_generators_follow_the_recipe():
     assert len(np.unique(pages)) == len(pages)          # no page shared
     full = W.config_ctx_lens(4)
     assert full.min() >= 8192 and full.max() <= 65536 and len(full) == 16
+
+
+# --------------------------------------------------------------------------- ragged draft counts
+def _ragged_case():
+    r = np.random.Generator(np.random.Philox(key=77))
+    trees = [W.random_tree(12, 5, r) for _ in range(3)]
+    return W.make_case("ragged", 55, dtype=W.DT_BF16, Hq=4, Hkv=2, D=32, ctx_lens=[40, 7, 19], trees=trees)
+
+
+def test_ragged_with_full_counts_is_the_plain_step(oracle_mod):
+    oracle = oracle_mod
+    case = _ragged_case()
+    full = oracle.verify_attn_case(case)
+    assert np.array_equal(oracle.verify_attn_ragged_case(case, [case.N] * case.B), full)
+
+
+def test_ragged_rows_and_cache_rows_of_absent_nodes_do_not_matter(oracle_mod):
+    import dataclasses
+    oracle = oracle_mod
+    case = _ragged_case()
+    nd = [5, 0, 12]
+    out = oracle.verify_attn_ragged_case(case, nd)
+    assert (out[0, 5:] == 0).all() and (out[1] == 0).all()
+    assert np.isfinite(out).all() and np.abs(out[0, :5]).max() > 0
+    # a node's output depends on its ancestors only, and those precede it: the present rows
+    # equal the rows of the full step (pinned above by the non-ancestor invariance)
+    full = oracle.verify_attn_case(case)
+    assert np.array_equal(out[0, :5], full[0, :5]) and np.array_equal(out[2], full[2])
+    # scrambling q, the parents and the cached K/V rows of the absent nodes changes nothing
+    q2 = case.q.copy(); q2[0, 5:] = q2[0, 5:][::-1]; q2[1] = 0
+    par2 = case.tree_parent.copy(); par2[0, 5:] = 0; par2[1] = -1
+    k2 = case.k_pool.copy().reshape(-1); v2 = case.v_pool.copy().reshape(-1)
+    for b, n in enumerate(nd):
+        for j in range(n, case.N):
+            t = int(case.ctx_lens[b]) + j
+            pg = int(case.page_table[b, t // 16])
+            for g in range(case.Hkv):
+                off = pg * case.stride_page + g * case.stride_head + (t % 16) * case.stride_token
+                k2[off:off + case.D] = k2[off:off + case.D][::-1]
+                v2[off:off + case.D] = 0
+    other = dataclasses.replace(case, q=q2, tree_parent=par2, k_pool=k2.reshape(case.k_pool.shape),
+                                v_pool=v2.reshape(case.v_pool.shape))
+    assert np.array_equal(oracle.verify_attn_ragged_case(other, nd), out)
