@@ -65,6 +65,7 @@ typedef enum owl_dtype {
 #define OWL_DEV_BAD_PAGE 2u     /* a needed page id not in [0, n_pool_pages)      */
 #define OWL_DEV_BAD_CTX_LEN 4u  /* some ctx_lens[b] not in [0, max_ctx_len]       */
 #define OWL_DEV_BAD_ACCEPT 8u   /* accepted[] not a strictly increasing list in [0, n_draft) */
+#define OWL_DEV_BAD_NDRAFT 16u  /* some n_draft_seq[b] not in [0, n_draft]        */
 
 /*
  * Shape of one verify step.  Strides are in ELEMENTS of qkv_dtype.
@@ -158,6 +159,22 @@ owl_status owl_verify_attn_phases(const owl_verify_desc *desc, const void *q, co
                                   const int32_t *ctx_lens, const int32_t *tree_parent, float *out,
                                   void *workspace, size_t workspace_bytes, uint32_t *dev_status,
                                   void *stream, int32_t phases);
+
+/*
+ * owl_verify_attn for a batch whose sequences carry different numbers of drafted
+ * tokens (a verify step may mix sequence and tree drafts of different sizes,
+ * Algorithm 1).  n_draft_seq [B] int32 device: sequence b has the nodes
+ * 0 .. n_draft_seq[b]-1 of row b of q / tree_parent and draft K/V rows only at
+ * ctx_lens[b] .. ctx_lens[b] + n_draft_seq[b] - 1; entries of tree_parent, q
+ * and the cache beyond that are not interpreted.  Output rows of absent nodes
+ * are written as zeros.  Entries outside [0, n_draft] are forced into the range
+ * and flagged (OWL_DEV_BAD_NDRAFT).  Everything else as owl_verify_attn.
+ */
+owl_status owl_verify_attn_ragged(const owl_verify_desc *desc, const void *q, const void *k_cache,
+                                  const void *v_cache, const int32_t *page_table,
+                                  const int32_t *ctx_lens, const int32_t *tree_parent,
+                                  const int32_t *n_draft_seq, float *out, void *workspace,
+                                  size_t workspace_bytes, uint32_t *dev_status, void *stream);
 
 /*
  * The attention mask of a drafted tree in packed form (Sec. 3.2.2: "manipulating

@@ -18,13 +18,14 @@ OWL_OK = 0
 OWL_ERR_INVALID_ARG, OWL_ERR_BAD_TREE, OWL_ERR_TOO_MANY_DRAFT = -1, -2, -3
 OWL_ERR_UNSUPPORTED, OWL_ERR_WORKSPACE, OWL_ERR_HIP = -4, -5, -6
 OWL_DEV_BAD_PARENT, OWL_DEV_BAD_PAGE, OWL_DEV_BAD_CTX_LEN, OWL_DEV_BAD_ACCEPT = 1, 2, 4, 8
+OWL_DEV_BAD_NDRAFT = 16
 
 EXPORTS = (
     "owl_verify_attn_plan", "owl_verify_attn_workspace_size", "owl_verify_attn",
     "owl_verify_attn_phases", "owl_stream_read_probe", "owl_selftest_quad_max",
     "owl_gather_read_probe", "owl_debug_set_timeline",
     "owl_build_tree_mask", "owl_build_tree_mask_host", "owl_gather_kv",
-    "owl_prepare_spec_tree", "owl_accept_greedy", "owl_commit_kv",
+    "owl_prepare_spec_tree", "owl_accept_greedy", "owl_commit_kv", "owl_verify_attn_ragged",
     "owl_status_str", "owl_version",
 )
 
@@ -84,6 +85,9 @@ def lib() -> ctypes.CDLL:
         l.owl_verify_attn.restype = ctypes.c_int
         l.owl_verify_attn.argtypes = [ctypes.POINTER(VerifyDesc), vp, vp, vp, vp, vp, vp, vp,
                                       vp, ctypes.c_size_t, vp, vp]
+        l.owl_verify_attn_ragged.restype = ctypes.c_int
+        l.owl_verify_attn_ragged.argtypes = [ctypes.POINTER(VerifyDesc), vp, vp, vp, vp, vp, vp, vp, vp,
+                                             vp, ctypes.c_size_t, vp, vp]
         l.owl_verify_attn_phases.restype = ctypes.c_int
         l.owl_verify_attn_phases.argtypes = [ctypes.POINTER(VerifyDesc), vp, vp, vp, vp, vp, vp, vp,
                                              vp, ctypes.c_size_t, vp, vp, i32]
@@ -256,3 +260,12 @@ def owl_commit_kv(desc: VerifyDesc, k_cache, v_cache, page_table, ctx_lens, acce
                              _ptr(ctx_lens), _ptr(accepted), _ptr(n_accept), _ptr(new_ctx_lens),
                              _ptr(dev_status), _stream() if stream is None else stream)
     _check(rc, "owl_commit_kv")
+
+
+def owl_verify_attn_ragged(desc: VerifyDesc, q, k_cache, v_cache, page_table, ctx_lens, tree_parent, n_draft_seq,
+                           out, workspace, dev_status=None, stream: Optional[int] = None) -> None:
+    rc = lib().owl_verify_attn_ragged(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(page_table),
+                                      _ptr(ctx_lens), _ptr(tree_parent), _ptr(n_draft_seq), _ptr(out),
+                                      _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                      _ptr(dev_status), _stream() if stream is None else stream)
+    _check(rc, "owl_verify_attn_ragged")

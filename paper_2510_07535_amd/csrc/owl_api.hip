@@ -179,11 +179,38 @@ owl_status owl_verify_attn(const owl_verify_desc *desc, const void *q, const voi
                                   workspace, workspace_bytes, dev_status, stream, OWL_PHASE_ALL);
 }
 
+static owl_status verify_impl(const owl_verify_desc *desc, const void *q, const void *k_cache,
+                              const void *v_cache, const int32_t *page_table, const int32_t *ctx_lens,
+                              const int32_t *tree_parent, const int32_t *n_draft_seq, float *out,
+                              void *workspace, size_t workspace_bytes, uint32_t *dev_status, void *stream,
+                              int32_t phases);
+
 owl_status owl_verify_attn_phases(const owl_verify_desc *desc, const void *q, const void *k_cache,
                                   const void *v_cache, const int32_t *page_table,
                                   const int32_t *ctx_lens, const int32_t *tree_parent, float *out,
                                   void *workspace, size_t workspace_bytes, uint32_t *dev_status,
                                   void *stream, int32_t phases)
+{
+    return verify_impl(desc, q, k_cache, v_cache, page_table, ctx_lens, tree_parent, nullptr, out, workspace,
+                       workspace_bytes, dev_status, stream, phases);
+}
+
+owl_status owl_verify_attn_ragged(const owl_verify_desc *desc, const void *q, const void *k_cache,
+                                  const void *v_cache, const int32_t *page_table,
+                                  const int32_t *ctx_lens, const int32_t *tree_parent,
+                                  const int32_t *n_draft_seq, float *out, void *workspace,
+                                  size_t workspace_bytes, uint32_t *dev_status, void *stream)
+{
+    if (!n_draft_seq) return OWL_ERR_INVALID_ARG;
+    return verify_impl(desc, q, k_cache, v_cache, page_table, ctx_lens, tree_parent, n_draft_seq, out,
+                       workspace, workspace_bytes, dev_status, stream, OWL_PHASE_ALL);
+}
+
+static owl_status verify_impl(const owl_verify_desc *desc, const void *q, const void *k_cache,
+                              const void *v_cache, const int32_t *page_table, const int32_t *ctx_lens,
+                              const int32_t *tree_parent, const int32_t *n_draft_seq, float *out,
+                              void *workspace, size_t workspace_bytes, uint32_t *dev_status, void *stream,
+                              int32_t phases)
 {
     if (phases < 1 || phases > OWL_PHASE_ALL) return OWL_ERR_INVALID_ARG;
     FullPlan fp;
@@ -205,6 +232,7 @@ owl_status owl_verify_attn_phases(const owl_verify_desc *desc, const void *q, co
     memset(&p, 0, sizeof p);
     p.q = q; p.k = k_cache; p.v = v_cache;
     p.page_table = page_table; p.ctx_lens = ctx_lens; p.parent = tree_parent;
+    p.n_draft_seq = n_draft_seq;
     p.part_o = static_cast<float *>(workspace);
     p.part_ml = reinterpret_cast<float *>(static_cast<char *>(workspace) + fp.part_o_bytes);
     p.out = out;

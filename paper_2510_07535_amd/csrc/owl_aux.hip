@@ -28,7 +28,8 @@ __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
     const int j = lane & 15, qd = lane >> 4;
 
     const int L = load_ctx_len(p.ctx_lens, b, p.max_ctx_len, nullptr);
-    const int ns = (L + p.N + p.C - 1) / p.C;
+    const int Nb = load_n_draft(p.n_draft_seq, b, p.N, nullptr);
+    const int ns = Nb == 0 ? 0 : (L + Nb + p.C - 1) / p.C;        // a sequence without drafts wrote no partials
     const size_t slot0 = (((size_t)b * p.Hkv + g) * p.max_splits) * p.RT + tg;
 
     float mw = -INFINITY, lw = 0.f;
@@ -80,12 +81,13 @@ __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
     const int row = tg * kRowTile + j;
     if (row >= p.R) return;
     const int i = row / p.G, hh = row % p.G;
-    const float inv = 1.0f / lsum;
+    const float inv = i < Nb ? 1.0f / lsum : 0.f;                   // rows of absent nodes come out as zeros
     float *o = p.out + (((int64_t)b * p.N + i) * p.Hq + g * p.G + hh) * D + 4 * qd;
 #pragma unroll
     for (int u = 0; u < UPW; ++u)
         *reinterpret_cast<float4 *>(o + 16 * (u0 + u)) =
-            make_float4(tot[u].x * inv, tot[u].y * inv, tot[u].z * inv, tot[u].w * inv);
+            i < Nb ? make_float4(tot[u].x * inv, tot[u].y * inv, tot[u].z * inv, tot[u].w * inv)
+                   : make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
 hipError_t launch_combine(const KParams &p, int D, hipStream_t s)

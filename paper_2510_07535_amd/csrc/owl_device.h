@@ -22,6 +22,19 @@ __device__ __forceinline__ int load_ctx_len(const int32_t *ctx_lens, int b, int 
     return L;
 }
 
+// Number of drafted tokens of sequence b: N unless a per-sequence array is given,
+// whose entries are forced into [0, N].
+__device__ __forceinline__ int load_n_draft(const int32_t *n_draft_seq, int b, int N, uint32_t *st)
+{
+    if (!n_draft_seq) return N;
+    int n = n_draft_seq[b];
+    if (n < 0 || n > N) {
+        flag_status(st, OWL_DEV_BAD_NDRAFT);
+        n = n < 0 ? 0 : N;
+    }
+    return n;
+}
+
 // Physical page of logical page lp of sequence b; an id outside the pool (or a
 // logical page beyond the table) is replaced by page 0 and flagged.
 __device__ __forceinline__ int load_page(const int32_t *page_table, int b, int max_pages,

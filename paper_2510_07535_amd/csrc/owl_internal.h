@@ -19,6 +19,7 @@ constexpr int kSplitQuantum = 64;         // split_tokens is a multiple of every
 struct KParams {
     const void *q, *k, *v;
     const int32_t *page_table, *ctx_lens, *parent;
+    const int32_t *n_draft_seq;   // optional [B]: drafted tokens of each sequence (<= N), else null = N everywhere
     float *part_o;        // split partials: accumulator fragments
     float *part_ml;       // split partials: running reference m and row sum l
     float *out;

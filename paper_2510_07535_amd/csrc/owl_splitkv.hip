@@ -218,6 +218,10 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     // first, so that all of the kernel's set-up reads are in flight together:
     // raw page-table entries of this split's window, the parent array, Q ----
     const int pos0 = c * p.C;
+    // drafted tokens of this sequence (a batch may mix tree sizes): rows of nodes >= Nb are
+    // idle, their K/V rows are not part of the sequence, and the combine writes zeros for them
+    const int Nb = load_n_draft(p.n_draft_seq, b, p.N, p.dev_status);
+    if (Nb == 0) return;
     const int win_pages = p.C / kPage;               // pages a full split spans (<= kMaxPagesPerSplit)
     int raw_page[kMaxPagesPerSplit / kThreads];
 #pragma unroll
@@ -241,7 +245,7 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
         const bool tile_ok = tg < p.RT;
         my_nt += tile_ok ? 1 : 0;
         const int row = tg * kRowTile + j;
-        const bool ok = tile_ok && row < p.R;
+        const bool ok = tile_ok && row < p.R && row / p.G < Nb;
         const int i = ok ? row / p.G : 0;
         const int hh = ok ? row % p.G : 0;
         irow[t] = ok ? i : -1;
@@ -262,7 +266,7 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
 
 
     const int L = load_ctx_len(p.ctx_lens, b, p.max_ctx_len, p.dev_status);
-    const int Ttot = L + p.N;
+    const int Ttot = L + Nb;
     if (pos0 >= Ttot) return;                       // this split does not exist for b
     const int pos1 = min(pos0 + p.C, Ttot);
     const int nstages = (pos1 - pos0 + SK - 1) / SK;
@@ -287,7 +291,7 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     const bool has_drafts = pos1 > L;               // uniform over the workgroup
     __syncthreads();
     if (has_drafts) {
-        if (tid < p.N) s_anc[tid] = ancestor_set(s_parent, tid, nullptr, p.dev_status);
+        if (tid < Nb) s_anc[tid] = ancestor_set(s_parent, tid, nullptr, p.dev_status);
         __syncthreads();
     }
     stamp(1);

@@ -152,3 +152,12 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode == 2
     assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_ragged_entry_point_rejects_null_counts():
+    lib = B.lib()
+    d = _good()
+    need = B.owl_verify_attn_workspace_size(d)
+    A = 0x10000
+    assert lib.owl_verify_attn_ragged(ctypes.byref(d), A, A, A, A, A, A, None, A, A, need, None, None) == B.OWL_ERR_INVALID_ARG
+    assert lib.owl_verify_attn_ragged(ctypes.byref(d), A, A, A, A, A, A, A, A, None, need, None, None) == B.OWL_ERR_WORKSPACE

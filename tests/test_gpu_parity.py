@@ -318,3 +318,47 @@ def test_device_side_errors_are_flagged():
     B.owl_build_tree_mask(par, anc, None, st)
     torch.cuda.synchronize()
     assert int(st.item()) & B.OWL_DEV_BAD_PARENT
+
+
+# ---------------------------------------------------------------------------
+# per-sequence draft counts
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,N,G,counts", [
+    (W.DT_BF16, 26, 4, [26, 0, 9, 1, 17]),          # 7 row tiles, one sequence without drafts
+    (W.DT_BF16, 60, 4, [60, 31, 2]),                # 15 row tiles (pipelined loop)
+    (W.DT_BF16, 40, 8, [40, 13]),                   # 20 row tiles (three tiles per wave)
+    (W.DT_BF16, 6, 4, [3, 6, 1, 5]),                # 2 row tiles (two key groups)
+    (W.DT_F32, 10, 4, [4, 10]),
+])
+def test_ragged_draft_counts(oracle_mod, dtype, N, G, counts):
+    r = _rng(900 + N)
+    B_ = len(counts)
+    ctx = [int(x) for x in r.integers(0, 3000, size=B_)]
+    ctx[0] = 2500
+    D = 64 if dtype == W.DT_F32 else 128
+    case = W.make_case("ragged", 300 + N, dtype=dtype, Hq=2 * G, Hkv=2, D=D, ctx_lens=ctx,
+                       trees=[W.random_tree(N, 6, r) for _ in range(B_)])
+    want = oracle_mod.verify_attn_ragged_case(case, counts)
+    for split in (0, 192):
+        step = VerifyStep(case, split_tokens=split)
+        nd = torch.tensor(counts, dtype=torch.int32, device=step.device)
+        step.out.fill_(float("nan"))
+        B.owl_verify_attn_ragged(step.desc, step.q, step.k, step.v, step.page_table, step.ctx_lens,
+                                 step.tree_parent, nd, step.out, step.workspace, step.status)
+        got = step.result()
+        assert step.dev_status() == 0
+        assert_close(got, want, case.dtype, f"ragged N={N} split={split}")
+        for b, n in enumerate(counts):
+            assert (got[b, n:] == 0).all()
+
+
+def test_ragged_flags_bad_counts():
+    case = W.make_case("ragged_bad", 77, dtype=W.DT_BF16, Hq=8, Hkv=2, D=128, ctx_lens=[300, 200],
+                       trees=[W.chain_tree(5) for _ in range(2)])
+    step = VerifyStep(case)
+    nd = torch.tensor([9, -1], dtype=torch.int32, device=step.device)
+    B.owl_verify_attn_ragged(step.desc, step.q, step.k, step.v, step.page_table, step.ctx_lens,
+                             step.tree_parent, nd, step.out, step.workspace, step.status)
+    got = step.result()
+    assert step.dev_status() & B.OWL_DEV_BAD_NDRAFT
+    assert np.isfinite(got).all() and (got[1] == 0).all()            # 9 -> 5 nodes, -1 -> none
