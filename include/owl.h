@@ -97,6 +97,10 @@ typedef struct owl_verify_desc {
 /* What the library decided for a descriptor; informational (bench, tests). */
 typedef struct owl_plan {
     int32_t split_tokens;    /* tokens of the logical sequence (prefix + drafts) per split */
+                             /* for a context of max_ctx_len.  With batch == 1 and a       */
+                             /* library-chosen size, a shorter context is cut on the device */
+                             /* into max_splits shorter splits instead (never below the    */
+                             /* planner's minimum), so that the launch still fills the chip */
     int32_t max_splits;      /* splits of the longest admissible sequence                  */
     int32_t rows_per_kv;     /* R = (Hq/Hkv) * N query rows packed against one KV stream   */
     int32_t row_tiles;       /* 16-row MFMA tiles covering R                               */

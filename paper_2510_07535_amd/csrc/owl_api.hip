@@ -56,6 +56,7 @@ struct FullPlan {
     owl_plan pub;
     const Variant *variant;
     size_t part_o_bytes, part_ml_bytes;
+    int32_t adapt, c_min;
 };
 
 owl_status make_plan(const owl_verify_desc *d, FullPlan *fp)
@@ -103,6 +104,15 @@ owl_status make_plan(const owl_verify_desc *d, FullPlan *fp)
     if (C > kMaxSplitTokens) C = kMaxSplitTokens;
     if (C < kSplitQuantum) C = kSplitQuantum;
     const int64_t max_splits = (T + C - 1) / C;
+    // One sequence and a library-chosen split size: the kernels cut a context
+    // shorter than max_ctx_len into the same number of splits (never below the
+    // minimum used above), so the launch still fills the chip.
+    fp->adapt = d->split_tokens == 0 && d->batch == 1;
+    {
+        int64_t cmin = align_up((size_t)(8 * R), kSplitQuantum);
+        if (cmin < 256) cmin = 256;
+        fp->c_min = (int32_t)(cmin < C ? cmin : C);
+    }
 
     const size_t slots = (size_t)d->batch * d->n_kv_heads * (size_t)max_splits * RT;
     fp->part_o_bytes = align_up(slots * (size_t)d->head_dim * kRowTile * sizeof(float), 256);
@@ -241,6 +251,7 @@ static owl_status verify_impl(const owl_verify_desc *desc, const void *q, const 
     p.G = p.Hq / p.Hkv; p.R = fp.pub.rows_per_kv;
     p.max_pages = desc->max_pages_per_seq; p.max_ctx_len = desc->max_ctx_len;
     p.C = fp.pub.split_tokens; p.max_splits = fp.pub.max_splits;
+    p.adapt = fp.adapt; p.c_min = fp.c_min;
     p.RT = fp.pub.row_tiles; p.row_groups = fp.pub.row_groups;
     p.stride_page = desc->kv_stride_page; p.stride_head = desc->kv_stride_head;
     p.stride_token = desc->kv_stride_token; p.n_pool_pages = desc->n_pool_pages;

@@ -29,7 +29,8 @@ __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
 
     const int L = load_ctx_len(p.ctx_lens, b, p.max_ctx_len, nullptr);
     const int Nb = load_n_draft(p.n_draft_seq, b, p.N, nullptr);
-    const int ns = Nb == 0 ? 0 : (L + Nb + p.C - 1) / p.C;        // a sequence without drafts wrote no partials
+    const int C = split_tokens_for(p, L + Nb);
+    const int ns = Nb == 0 ? 0 : (L + Nb + C - 1) / C;            // a sequence without drafts wrote no partials
     const size_t slot0 = (((size_t)b * p.Hkv + g) * p.max_splits) * p.RT + tg;
 
     float mw = -INFINITY, lw = 0.f;

@@ -35,6 +35,19 @@ __device__ __forceinline__ int load_n_draft(const int32_t *n_draft_seq, int b, i
     return n;
 }
 
+// Tokens per split for a sequence of T cached rows.  The host plans for the
+// longest context it was told about; a lone, shorter sequence is cut into the
+// same number of (shorter) splits instead of leaving most of the chip idle.
+// Never above p.C, never below the planner's minimum, a multiple of the stage.
+__device__ __forceinline__ int split_tokens_for(const KParams &p, int T)
+{
+    if (!p.adapt) return p.C;
+    int C = (T + p.max_splits - 1) / p.max_splits;
+    C = (C + kSplitQuantum - 1) / kSplitQuantum * kSplitQuantum;
+    C = max(C, p.c_min);
+    return min(C, p.C);
+}
+
 // Physical page of logical page lp of sequence b; an id outside the pool (or a
 // logical page beyond the table) is replaced by page 0 and flagged.
 __device__ __forceinline__ int load_page(const int32_t *page_table, int b, int max_pages,

@@ -26,7 +26,9 @@ struct KParams {
     uint32_t *dev_status;
     int32_t B, N, Hq, Hkv, G, R;
     int32_t max_pages, max_ctx_len;
-    int32_t C;            // tokens per split
+    int32_t C;            // tokens per split (an upper bound when `adapt` is set)
+    int32_t adapt;        // one sequence, library-chosen splits: the split size follows the actual length
+    int32_t c_min;        // smallest split size the planner allows
     int32_t max_splits;
     int32_t RT;           // row tiles covering R
     int32_t row_groups;

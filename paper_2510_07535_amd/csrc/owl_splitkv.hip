@@ -217,22 +217,26 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     // ---- everything that does not depend on the context length is requested
     // first, so that all of the kernel's set-up reads are in flight together:
     // raw page-table entries of this split's window, the parent array, Q ----
-    const int pos0 = c * p.C;
+    int C = p.C;                                      // revised below once the context length is known
+    int pos0 = c * C;
     // drafted tokens of this sequence (a batch may mix tree sizes): rows of nodes >= Nb are
     // idle, their K/V rows are not part of the sequence, and the combine writes zeros for them
     const int Nb = load_n_draft(p.n_draft_seq, b, p.N, p.dev_status);
     if (Nb == 0) return;
-    const int win_pages = p.C / kPage;               // pages a full split spans (<= kMaxPagesPerSplit)
     int raw_page[kMaxPagesPerSplit / kThreads];
+    auto request_pages = [&]() {
+        const int win_pages = C / kPage;             // pages a full split spans (<= kMaxPagesPerSplit)
 #pragma unroll
-    for (int r = 0; r < kMaxPagesPerSplit / kThreads; ++r) {
-        const int idx = tid + r * kThreads, lp = pos0 / kPage + idx;
-        raw_page[r] = -1;
-        if (idx < win_pages) {
-            if (!p.page_table) raw_page[r] = lp;
-            else if (lp < p.max_pages) raw_page[r] = p.page_table[(int64_t)b * p.max_pages + lp];
+        for (int r = 0; r < kMaxPagesPerSplit / kThreads; ++r) {
+            const int idx = tid + r * kThreads, lp = pos0 / kPage + idx;
+            raw_page[r] = -1;
+            if (idx < win_pages) {
+                if (!p.page_table) raw_page[r] = lp;
+                else if (lp < p.max_pages) raw_page[r] = p.page_table[(int64_t)b * p.max_pages + lp];
+            }
         }
-    }
+    };
+    request_pages();
     if (tid < p.N) s_parent[tid] = p.parent[(int64_t)b * p.N + tid];
     // ---- this wave's query rows: tiles wr, wr + WR, ... of the row group ----
     uint4 qf[TPW][KQ];
@@ -267,8 +271,13 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
 
     const int L = load_ctx_len(p.ctx_lens, b, p.max_ctx_len, p.dev_status);
     const int Ttot = L + Nb;
+    if (split_tokens_for(p, Ttot) != C) {           // uniform: a context shorter than planned for
+        C = split_tokens_for(p, Ttot);
+        pos0 = c * C;
+        request_pages();                            // the window moved: one more round trip
+    }
     if (pos0 >= Ttot) return;                       // this split does not exist for b
-    const int pos1 = min(pos0 + p.C, Ttot);
+    const int pos1 = min(pos0 + C, Ttot);
     const int nstages = (pos1 - pos0 + SK - 1) / SK;
 
     // ---- page list of this split (validated now that its extent is known),

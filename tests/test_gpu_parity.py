@@ -362,3 +362,25 @@ def test_ragged_flags_bad_counts():
     got = step.result()
     assert step.dev_status() & B.OWL_DEV_BAD_NDRAFT
     assert np.isfinite(got).all() and (got[1] == 0).all()            # 9 -> 5 nodes, -1 -> none
+
+
+# ---------------------------------------------------------------------------
+# a single sequence much shorter than the length the plan was made for
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("L,planned", [(0, 131072), (100, 131072), (3000, 131072), (40000, 65536), (5000, 5000), (4999, 5000)])
+def test_context_shorter_than_planned(oracle_mod, L, planned):
+    """The plan is sized by max_ctx_len; the kernels re-cut a shorter lone sequence into the
+    same number of splits.  Same result either way."""
+    case = W.make_case("short_ctx", 500 + L % 97, dtype=W.DT_BF16, Hq=8, Hkv=2, D=128, ctx_lens=[L],
+                       trees=[W.random_tree(14, 4, _rng(L + 1))])
+    want = oracle_mod.verify_attn_case(case)
+    # the page table has to cover the planned length: pad its row (the extra entries are never read)
+    import dataclasses
+    cols = (planned + case.N + 15) // 16
+    table = np.zeros((1, cols), dtype=np.int32)
+    table[:, :case.page_table.shape[1]] = case.page_table
+    wide = dataclasses.replace(case, page_table=table, max_pages_per_seq=cols)
+    got, step = _run(wide, max_ctx_len=planned)
+    assert_close(got, want, case.dtype, f"L={L} planned={planned} plan={step.plan.as_dict()}")
+    exact, _ = _run(case)
+    assert_close(got, exact.astype(np.float64), case.dtype, "planned-for-longer vs planned-exactly")
