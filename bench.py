@@ -258,6 +258,13 @@ def main():
                      "kernel_median_us": main_res["split_kernel_median_s"] * 1e6,
                      "algorithmic_bytes_per_launch": kbytes},
     }
+    # the same kernel against the matrix pipe: QK^T and PV are 2*D flop each per (row, key); the
+    # long-context tree shapes sit at the ridge between the two roofs
+    rows_per_kv = (case.Hq // case.Hkv) * case.N
+    flop = 4.0 * case.D * rows_per_kv * case.Hkv * float((case.ctx_lens.astype("int64") + case.N).sum())
+    line["roofline"]["mfma"] = {"achieved": flop / main_res["split_kernel_avg_s"] / 1e12, "peak": 2500.0,
+                                "unit": "TFLOP/s", "frac": flop / main_res["split_kernel_avg_s"] / 2.5e15,
+                                "algorithmic_flop_per_launch": flop}
     if not args.no_probe:
         line["roofline"]["stream_read_probe_GBps"] = stream_probe_gbs()
     if args.all:
