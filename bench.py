@@ -132,6 +132,27 @@ def stream_probe_gbs(nbytes=1 << 30):
     return best
 
 
+def mfma_probe_tflops(kind="random", iters=20000):
+    """Sustained bf16 MFMA rate of the whole chip on operands of the given kind."""
+    import torch
+    from paper_2510_07535_amd import binding as B
+    n = 1 << 19
+    if kind == "random":
+        src = (torch.randn(n, device="cuda") * 1.0).to(torch.bfloat16)
+    else:
+        src = torch.ones(n, device="cuda", dtype=torch.bfloat16)
+    nwg = 256
+    sink = torch.zeros(nwg * 512, dtype=torch.float32, device="cuda")
+    B.owl_mfma_probe(src, 2000, sink, nwg)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    B.owl_mfma_probe(src, iters, sink, nwg)
+    b.record()
+    torch.cuda.synchronize()
+    return nwg * 8 * iters * 16 * 16384.0 / (a.elapsed_time(b) * 1e-3) / 1e12
+
+
 def cpu_baseline(case, budget_rows=None):
     import numpy as np
     import oracle
@@ -267,6 +288,8 @@ def main():
                                 "algorithmic_flop_per_launch": flop}
     if not args.no_probe:
         line["roofline"]["stream_read_probe_GBps"] = stream_probe_gbs()
+        line["roofline"]["mfma"]["probe_random_operands_TFLOPs"] = mfma_probe_tflops("random")
+        line["roofline"]["mfma"]["probe_constant_operands_TFLOPs"] = mfma_probe_tflops("ones")
     if args.all:
         others = []
         for idx in (1, 2, 3, 4):

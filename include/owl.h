@@ -280,6 +280,17 @@ owl_status owl_stream_read_probe(const void *src, size_t bytes, uint32_t *sink,
                                  int32_t n_workgroups, void *stream);
 
 /*
+ * Measurement aid: the sustained rate of the matrix pipe.  n_workgroups
+ * workgroups of 8 wavefronts issue `iters` x 16 bf16 16x16x32 MFMAs per lane on
+ * operands read once from src (`bytes` bytes, a multiple of 16, 16-byte aligned,
+ * interpreted as bf16 values; their bit patterns matter: under its power limit
+ * this chip sustains a lower rate on random values than on constants).  Flop =
+ * n_workgroups * 8 * iters * 16 * 16384.  sink: n_workgroups * 512 floats, device.
+ */
+owl_status owl_mfma_probe(const void *src, size_t bytes, int32_t iters, float *sink, int32_t n_workgroups,
+                          void *stream);
+
+/*
  * Measurement aid: like owl_stream_read_probe, but the buffer is read in
  * 4 KiB blocks in the order block_order[0 .. n_blocks-1] (device int32, every
  * entry in [0, buffer bytes / 4096)).  With a random order this is the access

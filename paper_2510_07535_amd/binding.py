@@ -23,7 +23,7 @@ OWL_DEV_BAD_NDRAFT = 16
 EXPORTS = (
     "owl_verify_attn_plan", "owl_verify_attn_workspace_size", "owl_verify_attn",
     "owl_verify_attn_phases", "owl_stream_read_probe", "owl_selftest_quad_max",
-    "owl_gather_read_probe", "owl_debug_set_timeline",
+    "owl_gather_read_probe", "owl_debug_set_timeline", "owl_mfma_probe",
     "owl_build_tree_mask", "owl_build_tree_mask_host", "owl_gather_kv",
     "owl_prepare_spec_tree", "owl_accept_greedy", "owl_commit_kv", "owl_verify_attn_ragged",
     "owl_status_str", "owl_version",
@@ -93,6 +93,8 @@ def lib() -> ctypes.CDLL:
                                              vp, ctypes.c_size_t, vp, vp, i32]
         l.owl_stream_read_probe.restype = ctypes.c_int
         l.owl_stream_read_probe.argtypes = [vp, ctypes.c_size_t, vp, i32, vp]
+        l.owl_mfma_probe.restype = ctypes.c_int
+        l.owl_mfma_probe.argtypes = [vp, ctypes.c_size_t, i32, vp, i32, vp]
         l.owl_gather_read_probe.restype = ctypes.c_int
         l.owl_gather_read_probe.argtypes = [vp, vp, i32, vp, i32, vp]
         l.owl_debug_set_timeline.restype = ctypes.c_int
@@ -269,3 +271,9 @@ def owl_verify_attn_ragged(desc: VerifyDesc, q, k_cache, v_cache, page_table, ct
                                       _ptr(workspace), workspace.numel() * workspace.element_size(),
                                       _ptr(dev_status), _stream() if stream is None else stream)
     _check(rc, "owl_verify_attn_ragged")
+
+
+def owl_mfma_probe(src, iters: int, sink, n_workgroups: int, stream: Optional[int] = None) -> None:
+    rc = lib().owl_mfma_probe(_ptr(src), src.numel() * src.element_size(), iters, _ptr(sink), n_workgroups,
+                              _stream() if stream is None else stream)
+    _check(rc, "owl_mfma_probe")

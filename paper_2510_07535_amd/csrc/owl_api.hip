@@ -368,6 +368,18 @@ owl_status owl_stream_read_probe(const void *src, size_t bytes, uint32_t *sink,
     return OWL_OK;
 }
 
+owl_status owl_mfma_probe(const void *src, size_t bytes, int32_t iters, float *sink, int32_t n_workgroups,
+                          void *stream)
+{
+    if (!src || !sink || n_workgroups < 1 || iters < 1 || bytes < 16 || bytes % 16 != 0 ||
+        bytes / 16 > 0x7fffffff)
+        return OWL_ERR_INVALID_ARG;
+    if (misaligned(src, 16)) return OWL_ERR_INVALID_ARG;
+    if (launch_mfma_probe(src, bytes, iters, sink, n_workgroups, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return OWL_ERR_HIP;
+    return OWL_OK;
+}
+
 owl_status owl_gather_read_probe(const void *src, const int32_t *block_order, int32_t n_blocks,
                                  uint32_t *sink, int32_t n_workgroups, void *stream)
 {

@@ -230,6 +230,49 @@ hipError_t launch_gather_read(const void *src, const int32_t *perm, int n_blocks
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Matrix-pipe probe: 8 wavefronts per workgroup, each issuing nothing but
+// 16x16x32 bf16 MFMAs on operands taken once from `src` (so their bit patterns
+// are the caller's: the sustained rate of this chip depends on them).  16
+// independent accumulators per lane; sums are scaled down now and then to stay
+// finite.  2 * 16*16*32 flop per MFMA, 16 MFMAs per lane and iteration.
+// ---------------------------------------------------------------------------
+typedef float probe_f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
+
+__global__ void __launch_bounds__(512) mfma_probe_kernel(const uint4 *src, int n_vec, int iters, float *sink)
+{
+    uint4 a[8], b[2];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a[i] = src[(threadIdx.x * 8 + i) % n_vec];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) b[i] = src[(threadIdx.x * 2 + i + 77) % n_vec];
+    probe_f32x4 acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = probe_f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(probe_bf16x8, a[i & 7]),
+                                                             __builtin_bit_cast(probe_bf16x8, b[i >> 3]), acc[i], 0, 0, 0);
+        if ((it & 63) == 63) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] *= 1.0e-3f;
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += acc[i][0] + acc[i][3];
+    sink[blockIdx.x * 512 + threadIdx.x] = s;
+}
+
+hipError_t launch_mfma_probe(const void *src, size_t bytes, int iters, float *sink, int n_wg, hipStream_t s)
+{
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3(n_wg), dim3(512), 0, s, static_cast<const uint4 *>(src),
+                       (int)(bytes / 16), iters, sink);
+    return hipGetLastError();
+}
+
 hipError_t launch_stream_read(const void *src, size_t bytes, uint32_t *sink, int n_wg, hipStream_t s)
 {
     hipLaunchKernelGGL(stream_read_kernel, dim3(n_wg), dim3(256), 0, s,

@@ -63,6 +63,7 @@ hipError_t launch_gather(const owl_verify_desc &d, const void *cache, const int3
                          int seq, int64_t first, int64_t n, void *dst, uint32_t *status,
                          hipStream_t s);
 
+hipError_t launch_mfma_probe(const void *src, size_t bytes, int iters, float *sink, int n_wg, hipStream_t s);
 hipError_t launch_gather_read(const void *src, const int32_t *perm, int n_blocks, uint32_t *sink,
                               int n_wg, hipStream_t s);
 hipError_t launch_quad_max(const float *in, float *out, hipStream_t s);

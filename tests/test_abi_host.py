@@ -161,3 +161,13 @@ def test_ragged_entry_point_rejects_null_counts():
     A = 0x10000
     assert lib.owl_verify_attn_ragged(ctypes.byref(d), A, A, A, A, A, A, None, A, A, need, None, None) == B.OWL_ERR_INVALID_ARG
     assert lib.owl_verify_attn_ragged(ctypes.byref(d), A, A, A, A, A, A, A, A, None, need, None, None) == B.OWL_ERR_WORKSPACE
+
+
+def test_mfma_probe_rejects_before_launch():
+    lib = B.lib()
+    A = 0x10000
+    assert lib.owl_mfma_probe(None, 4096, 10, A, 4, None) == B.OWL_ERR_INVALID_ARG
+    assert lib.owl_mfma_probe(A, 4096, 10, None, 4, None) == B.OWL_ERR_INVALID_ARG
+    assert lib.owl_mfma_probe(A, 4100, 10, A, 4, None) == B.OWL_ERR_INVALID_ARG       # not a multiple of 16
+    assert lib.owl_mfma_probe(A, 4096, 0, A, 4, None) == B.OWL_ERR_INVALID_ARG
+    assert lib.owl_mfma_probe(A + 4, 4096, 10, A, 4, None) == B.OWL_ERR_INVALID_ARG

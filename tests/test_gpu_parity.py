@@ -272,6 +272,14 @@ def test_measurement_aids():
     torch.cuda.synchronize()
     assert int(np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32)[:5])) == want
 
+    # the matrix-pipe probe: operands all 1.0 -> every accumulator is 32 per MFMA, 16 MFMAs deep per
+    # iteration and lane: after 3 iterations sink = acc[i][0] + acc[i][3] summed over 16 accumulators
+    ones = torch.ones(4096, dtype=torch.bfloat16, device="cuda")
+    fs = torch.zeros(2 * 512, dtype=torch.float32, device="cuda")
+    B.owl_mfma_probe(ones, 3, fs, 2)
+    torch.cuda.synchronize()
+    assert (fs.cpu().numpy() == 16 * 2 * 3 * 32.0).all()
+
     case = W.make_case("tl", 79, dtype=W.DT_BF16, Hq=32, Hkv=8, D=128, ctx_lens=[3000], trees=[W.random_tree(20, 4, r)])
     step = VerifyStep(case, split_tokens=512)
     step.run()
