@@ -392,3 +392,20 @@ def test_context_shorter_than_planned(oracle_mod, L, planned):
     assert_close(got, want, case.dtype, f"L={L} planned={planned} plan={step.plan.as_dict()}")
     exact, _ = _run(case)
     assert_close(got, exact.astype(np.float64), case.dtype, "planned-for-longer vs planned-exactly")
+
+
+# ---------------------------------------------------------------------------
+# a context near the upper end: one million tokens, pools beyond 2^31 bytes
+# ---------------------------------------------------------------------------
+def test_million_token_context(oracle_mod):
+    """64-bit addressing of the pool (beyond 2^31 bytes), 68 splits per KV head, page ids above 2^16."""
+    L = 1_100_003
+    case = W.make_case("ctx_1m", 4242, dtype=W.DT_BF16, Hq=16, Hkv=8, D=128, ctx_lens=[L],
+                       trees=[W.random_tree(10, 4, _rng(3))])
+    assert case.k_pool.nbytes > 2**31
+    got, step = _run(case)
+    rows = sample_rows(case, 10, seed=9, always=[(0, 0, 0), (0, case.N - 1, case.Hq - 1)])
+    want = oracle_mod.verify_attn_case(case, rows=rows)
+    sub = np.stack([got[b, i, h] for b, i, h in rows])
+    assert_close(sub, want, case.dtype, f"plan={step.plan.as_dict()}")
+    assert np.isfinite(got).all()
