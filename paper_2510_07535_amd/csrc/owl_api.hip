@@ -259,7 +259,7 @@ static owl_status verify_impl(const owl_verify_desc *desc, const void *q, const 
     p.timeline = g_timeline;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    dim3 grid(p.max_splits, p.Hkv * p.row_groups, p.B);
+    dim3 grid(p.Hkv * p.row_groups, p.max_splits, p.B);   // heads fastest: see the kernel's block-index comment
     if (phases & OWL_PHASE_SPLIT) {
         fp.variant->launch(p, grid, s);
         if (hipGetLastError() != hipSuccess) return OWL_ERR_HIP;

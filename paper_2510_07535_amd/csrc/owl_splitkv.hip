@@ -194,8 +194,11 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     const int wr = wave % WR, wk = wave / WR;
     const int j = lane & 15, qd = lane >> 4;
 
-    const int c = blockIdx.x;
-    const int g = blockIdx.y / p.row_groups, rg = blockIdx.y % p.row_groups;
+    // Workgroups go to the chip's eight XCDs round-robin in launch order, whether or not
+    // they have work.  KV heads (all with the same amount of work) vary fastest, so that
+    // splits that do not exist for a short sequence do not leave whole XCDs idle.
+    const int c = blockIdx.y;
+    const int g = blockIdx.x / p.row_groups, rg = blockIdx.x % p.row_groups;
     const int b = blockIdx.z;
 
     // optional timeline of this workgroup (profiling aid)
