@@ -198,7 +198,10 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     // they have work.  KV heads (all with the same amount of work) vary fastest, so that
     // splits that do not exist for a short sequence do not leave whole XCDs idle.
     const int c = blockIdx.y;
-    const int g = blockIdx.x / p.row_groups, rg = blockIdx.x % p.row_groups;
+    // Row groups that share a KV split (more than 24 row tiles) sit Hkv apart in x: with 8 KV
+    // heads they land on the same XCD at about the same time, and the second reads the split
+    // from that XCD's L2.
+    const int g = blockIdx.x % p.Hkv, rg = blockIdx.x / p.Hkv;
     const int b = blockIdx.z;
 
     // optional timeline of this workgroup (profiling aid)
