@@ -314,3 +314,62 @@ def make_config(idx: int, seed: Optional[int] = None, ctx_scale: float = 1.0, dt
         return make_case(name, seed, dtype=DT_BF16, Hq=32, Hkv=8, D=128, ctx_lens=ctx,
                          trees=[random_tree(26, 5, trng) for _ in range(len(ctx))])
     raise ValueError(idx)
+
+
+# ----------------------------------------------------------------------------
+# inputs of the drafter's recurrent cell (Sec. 3.2.1): random weights of the
+# paper's width (Sec. 4.1: d = 12288), random states and tokens.  Data only.
+# ----------------------------------------------------------------------------
+@dataclasses.dataclass
+class DrafterCase:
+    name: str
+    seed: int
+    dtype: int                   # storage type of h, W, E (DT_BF16 or DT_F16)
+    d_in: int
+    d: int
+    P: int                       # distinct parent states
+    M: int                       # rows of the step (children)
+    vocab: int
+    h: np.ndarray                # [P, d_in]   dtype bits
+    z: np.ndarray                # [P, d]      float32
+    W: np.ndarray                # [4, d, d_in] dtype bits, gates in the order f, i, o, c
+    E: np.ndarray                # [vocab, d]  dtype bits
+    tokens: np.ndarray           # [M] int32
+    parent_row: Optional[np.ndarray]   # [M] int32 or None (identity)
+    gamma_c: np.ndarray          # [d] float32, affine pair of the normalisation of the candidate
+    beta_c: np.ndarray
+    gamma_z: np.ndarray          # [d] float32, affine pair of the normalisation of the cell state
+    beta_z: np.ndarray
+    eps: float
+
+    def weight_bytes(self) -> int:
+        return 4 * self.d * self.d_in * 2
+
+
+def make_drafter_case(name: str, seed: int, *, dtype: int = DT_BF16, d_in: int, d: int, P: int, M: int,
+                      vocab: int = 1000, identity: bool = False, zero_state: bool = False,
+                      eps: float = 1e-5) -> DrafterCase:
+    """W ~ N(0, 1/d_in) so that the projections are O(1); h, E ~ N(0, 1);
+    z ~ N(0, 1) (zeros with ``zero_state``: the paper starts the cell state at
+    zero); the affine pairs are 1 + 0.1 N(0,1) and 0.1 N(0,1).  ``identity``
+    leaves parent_row out (row r continues state r; needs M == P)."""
+    if dtype not in (DT_BF16, DT_F16):
+        raise ValueError("the cell's storage type is bf16 or fp16")
+    rng = np.random.Generator(np.random.Philox(key=seed ^ 0xD4AF))
+    W = np.empty((4, d, d_in), dtype=np.uint16)
+    for m in range(4):                                       # gate by gate: bounds the fp32 transient
+        W[m] = store(_normal(rng, (d, d_in)) * np.float32(1.0 / math.sqrt(d_in)), dtype)
+    h = store(_normal(rng, (P, d_in)), dtype)
+    z = np.zeros((P, d), np.float32) if zero_state else _normal(rng, (P, d))
+    E = store(_normal(rng, (vocab, d)), dtype)
+    tokens = rng.integers(0, vocab, size=M).astype(np.int32)
+    if identity:
+        if M != P:
+            raise ValueError("identity needs M == P")
+        parent_row = None
+    else:
+        parent_row = rng.integers(0, P, size=M).astype(np.int32)
+    aff = [(_normal(rng, (d,)) * np.float32(0.1)) for _ in range(4)]
+    return DrafterCase(name=name, seed=seed, dtype=dtype, d_in=d_in, d=d, P=P, M=M, vocab=vocab, h=h, z=z, W=W,
+                       E=E, tokens=tokens, parent_row=parent_row, gamma_c=aff[0] + np.float32(1.0), beta_c=aff[1],
+                       gamma_z=aff[2] + np.float32(1.0), beta_z=aff[3], eps=eps)
