@@ -54,6 +54,8 @@ def parse():
     ap.add_argument("--split-tokens", type=int, default=0, help="override the library's split size (tuning)")
     ap.add_argument("--dtype", choices=("bf16", "f16"), default="bf16",
                     help="storage type of q/K/V (the configurations list bf16; f16 is the paper's type)")
+    ap.add_argument("--drafter", action="store_true",
+                    help="also time the drafter's recurrent cell (reported under 'drafter_cell'; implied by --all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
     return ap.parse_args()
@@ -232,6 +234,73 @@ def bench_steps(reps=200):
     return res
 
 
+DRAFTER_SHAPES = (
+    # name, d_in, d, states, rows: the paper's cell width (Sec. 4.1) with the ten rows of one tree
+    # level (Appendix A.1: top-k 10); square W is the shape the recurrence needs, 4096 / 8192 are
+    # the hidden sizes of the two target models feeding the first step
+    ("owl_cell_d12288_square_level10", 12288, 12288, 10, 10),
+    ("owl_cell_d12288_from8192_root10", 8192, 12288, 1, 10),
+    ("owl_cell_d12288_from4096_root10", 4096, 12288, 1, 10),
+)
+
+
+def bench_drafter(steps=60, with_cpu=True):
+    """The drafter's recurrent cell (one step = projection kernel + gate kernel) on random
+    weights: us per step and achieved GB/s over the 4 d d_in weight bytes, the projection
+    kernel alone against the HBM peak, and the oracle on the host for the same step."""
+    import torch
+    from paper_2510_07535_amd import binding as B
+    from paper_2510_07535_amd import workloads as W
+    from paper_2510_07535_amd.runner import DrafterStep
+    out = []
+    for name, d_in, d, P, M in DRAFTER_SHAPES:
+        case = W.make_drafter_case(name, 31, d_in=d_in, d=d, P=P, M=M, vocab=2048)
+        alpha = B.owl_drafter_alpha(8, d)
+        step = DrafterStep(case, alpha)
+        wbytes = case.weight_bytes()
+        copies = [step.w] + [step.w.clone() for _ in range(max(1, -(-MIN_ROTATION_BYTES // wbytes)) )]
+        k = [0]
+
+        def run(phases=3):
+            step.run(w=copies[k[0] % len(copies)], phases=phases)
+            k[0] += 1
+        for _ in range(5):
+            run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            run()
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / steps
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        for a, b in ev:
+            a.record()
+            run(phases=1)
+            b.record()
+            run(phases=2)
+        torch.cuda.synchronize()
+        ksec = sum(a.elapsed_time(b) for a, b in ev) / len(ev) * 1e-3
+        assert step.dev_status() == 0
+        res = {"workload": name, "d_in": d_in, "d": d, "n_states": P, "n_rows": M, "dtype": "bf16",
+               "weight_bytes": wbytes, "weight_copies_rotated": len(copies), "us_per_step": sec * 1e6,
+               "GBps": wbytes / sec / 1e9,
+               "roofline": {"bound": "hbm", "achieved": wbytes / ksec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": wbytes / ksec / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                            "kernel": "drafter_proj_kernel", "kernel_avg_us": ksec * 1e6,
+                            "algorithmic_bytes_per_launch": wbytes}}
+        if with_cpu and name == DRAFTER_SHAPES[0][0]:
+            from oracle import drafter as OD
+            t0 = time.perf_counter()
+            OD.drafter_cell_case(case, alpha)
+            dt = time.perf_counter() - t0
+            res["cpu_baseline"] = {"value": wbytes / dt / 1e9, "unit": "GB/s", "cores": os.cpu_count(),
+                                   "kind": "oracle", "sample": f"the whole step once ({dt:.1f} s)"}
+        out.append(res)
+        del step, copies
+        torch.cuda.empty_cache()
+    return out
+
+
 def bench_config(idx, args, want_detail):
     from paper_2510_07535_amd import workloads as W
     case = W.make_config(idx, dtype={"bf16": W.DT_BF16, "f16": W.DT_F16}[args.dtype])
@@ -306,6 +375,8 @@ def main():
             others.append(r)
         line["others"] = others
         line["step_kernels"] = bench_steps()
+    if args.all or args.drafter:
+        line["drafter_cell"] = bench_drafter(with_cpu=not args.no_cpu_baseline)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(case)
     else:

@@ -66,6 +66,8 @@ typedef enum owl_dtype {
 #define OWL_DEV_BAD_CTX_LEN 4u  /* some ctx_lens[b] not in [0, max_ctx_len]       */
 #define OWL_DEV_BAD_ACCEPT 8u   /* accepted[] not a strictly increasing list in [0, n_draft) */
 #define OWL_DEV_BAD_NDRAFT 16u  /* some n_draft_seq[b] not in [0, n_draft]        */
+#define OWL_DEV_BAD_TOKEN 32u   /* drafter cell: some tokens[r] not in [0, vocab)  */
+#define OWL_DEV_BAD_ROW 64u     /* drafter cell: some parent_row[r] not in [0, n_states) */
 
 /*
  * Shape of one verify step.  Strides are in ELEMENTS of qkv_dtype.
@@ -252,6 +254,82 @@ owl_status owl_accept_greedy(const int32_t *tokens, const int32_t *tree_parent, 
 owl_status owl_commit_kv(const owl_verify_desc *desc, void *k_cache, void *v_cache, const int32_t *page_table,
                          const int32_t *ctx_lens, const int32_t *accepted, const int32_t *n_accept,
                          int32_t *new_ctx_lens, uint32_t *dev_status, void *stream);
+
+/*
+ * One step of the drafter's recurrent cell (Sec. 3.2.1, Eq. 1-8): from the token
+ * t just predicted, the hidden state h it was predicted from and the running
+ * cell state z,
+ *     e   = E[t]                                                        (Eq. 1)
+ *     s^m = W^m h + alpha e                m in {f, i, o, c}            (Eq. 2)
+ *     g^m = sigmoid(s^m)                   m in {f, i, o}               (Eq. 5)
+ *     c   = f(s^c) g^i                                                  (Eq. 6)
+ *     z'  = z g^f + c                                                   (Eq. 7)
+ *     h'  = f(z') g^o                                                   (Eq. 8)
+ * where f is layer normalisation over the d channels (biased variance, eps under
+ * the root, optional affine pair) followed by the exact GeLU x Phi(x).  The cell
+ * never sees the context, so its cost does not depend on the context length
+ * (Sec. 3.2.1); the step is a single read of the 4 d d_in weights.
+ *
+ * A step handles n_rows <= 64 rows that continue n_states <= 64 distinct states:
+ * in tree drafting the children of a node share its (h, z) and differ in their
+ * token, so W^m h is formed once per state and row r uses state parent_row[r].
+ *
+ *   h          [n_states][d_in]  dtype (OWL_BF16 or OWL_F16)
+ *   z          [n_states][d]     float32 (all zeros at the first step, Sec. 3.2.1)
+ *   tokens     [n_rows] int32
+ *   parent_row [n_rows] int32, or NULL = identity (needs n_rows == n_states)
+ *   w          [4][d][d_in] dtype: W^f, W^i, W^o, W^c in this order, each stored
+ *              with one output channel's d_in weights contiguous; no bias
+ *   emb        [vocab][d] dtype, the embedding table E
+ *   gamma_c, beta_c, gamma_z, beta_z   [d] float32 each or NULL (1 resp. 0): the
+ *              affine pairs of f applied to s^c and of f applied to z'
+ *   h_out      [n_rows][d] dtype (h' rounded to nearest even: the next step's h
+ *              when d_in == d), h_out_f32 [n_rows][d] float32; either may be NULL
+ *   z_out      [n_rows][d] float32
+ *   workspace  >= owl_drafter_cell_workspace_size() bytes, 16-byte aligned
+ * Outputs must not overlap inputs.  d_in is a multiple of 32, d a multiple of 16
+ * and at most 16384.  A token outside [0, vocab) contributes e = 0 and is flagged
+ * (OWL_DEV_BAD_TOKEN); a parent_row outside [0, n_states) is read as 0 and flagged
+ * (OWL_DEV_BAD_ROW).  `phases`: OWL_DRAFTER_PROJ forms W^m h into the workspace,
+ * OWL_DRAFTER_GATES does the rest from the workspace; owl_drafter_cell runs both.
+ */
+typedef struct owl_drafter_desc {
+    int32_t d_in;       /* width of the incoming hidden state h                     */
+    int32_t d;          /* width of the cell (Sec. 4.1 uses 12288)                  */
+    int32_t n_states;   /* P in [1, 64]                                             */
+    int32_t n_rows;     /* M in [1, 64]                                             */
+    int32_t vocab;      /* rows of emb                                              */
+    int32_t dtype;      /* OWL_BF16 or OWL_F16: type of h, w, emb, h_out            */
+    float alpha;        /* weight of the embedding, e.g. from owl_drafter_alpha     */
+    float eps;          /* of the layer normalisation, e.g. 1e-5                    */
+} owl_drafter_desc;
+
+#define OWL_DRAFTER_PROJ 1
+#define OWL_DRAFTER_GATES 2
+#define OWL_DRAFTER_ALL 3
+
+owl_status owl_drafter_cell_workspace_size(const owl_drafter_desc *desc, size_t *bytes);
+
+owl_status owl_drafter_cell(const owl_drafter_desc *desc, const void *h, const float *z, const int32_t *tokens,
+                            const int32_t *parent_row, const void *w, const void *emb, const float *gamma_c,
+                            const float *beta_c, const float *gamma_z, const float *beta_z, void *h_out,
+                            float *h_out_f32, float *z_out, void *workspace, size_t workspace_bytes,
+                            uint32_t *dev_status, void *stream);
+
+owl_status owl_drafter_cell_phases(const owl_drafter_desc *desc, const void *h, const float *z,
+                                   const int32_t *tokens, const int32_t *parent_row, const void *w,
+                                   const void *emb, const float *gamma_c, const float *beta_c,
+                                   const float *gamma_z, const float *beta_z, void *h_out, float *h_out_f32,
+                                   float *z_out, void *workspace, size_t workspace_bytes, uint32_t *dev_status,
+                                   void *stream, int32_t phases);
+
+/*
+ * The weight of the embedding in Eq. 2, as Eq. 3-4 define it:
+ *     alpha_0 = 2^(-1 / (2 n)),   alpha = 2 alpha_0 / ((1 - alpha_0^2) d),
+ * n = the greatest tree depth to be drafted, d = the cell's width.  Host only;
+ * evaluated in double precision, *alpha_host receives it rounded to float.
+ */
+owl_status owl_drafter_alpha(int32_t max_depth, int32_t d, float *alpha_host);
 
 /* Host twin of owl_build_tree_mask for one tree; all pointers are HOST memory.
  * Validates the tree: OWL_ERR_BAD_TREE if some parent[i] is not in {-1} u [0,i). */

@@ -19,6 +19,8 @@ OWL_ERR_INVALID_ARG, OWL_ERR_BAD_TREE, OWL_ERR_TOO_MANY_DRAFT = -1, -2, -3
 OWL_ERR_UNSUPPORTED, OWL_ERR_WORKSPACE, OWL_ERR_HIP = -4, -5, -6
 OWL_DEV_BAD_PARENT, OWL_DEV_BAD_PAGE, OWL_DEV_BAD_CTX_LEN, OWL_DEV_BAD_ACCEPT = 1, 2, 4, 8
 OWL_DEV_BAD_NDRAFT = 16
+OWL_DEV_BAD_TOKEN, OWL_DEV_BAD_ROW = 32, 64
+OWL_DRAFTER_PROJ, OWL_DRAFTER_GATES, OWL_DRAFTER_ALL = 1, 2, 3
 
 EXPORTS = (
     "owl_verify_attn_plan", "owl_verify_attn_workspace_size", "owl_verify_attn",
@@ -26,6 +28,7 @@ EXPORTS = (
     "owl_gather_read_probe", "owl_debug_set_timeline", "owl_mfma_probe",
     "owl_build_tree_mask", "owl_build_tree_mask_host", "owl_gather_kv",
     "owl_prepare_spec_tree", "owl_accept_greedy", "owl_commit_kv", "owl_verify_attn_ragged",
+    "owl_drafter_cell", "owl_drafter_cell_phases", "owl_drafter_cell_workspace_size", "owl_drafter_alpha",
     "owl_status_str", "owl_version",
 )
 
@@ -56,6 +59,15 @@ class Plan(ctypes.Structure):
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class DrafterDesc(ctypes.Structure):
+    """Mirror of owl_drafter_desc."""
+    _fields_ = [
+        ("d_in", ctypes.c_int32), ("d", ctypes.c_int32), ("n_states", ctypes.c_int32),
+        ("n_rows", ctypes.c_int32), ("vocab", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("alpha", ctypes.c_float), ("eps", ctypes.c_float),
+    ]
 
 
 class OwlError(RuntimeError):
@@ -107,6 +119,14 @@ def lib() -> ctypes.CDLL:
         l.owl_build_tree_mask_host.argtypes = [vp, i32, vp, vp]
         l.owl_gather_kv.restype = ctypes.c_int
         l.owl_gather_kv.argtypes = [ctypes.POINTER(VerifyDesc), vp, vp, i32, i64, i64, vp, vp, vp]
+        l.owl_drafter_cell_workspace_size.restype = ctypes.c_int
+        l.owl_drafter_cell_workspace_size.argtypes = [ctypes.POINTER(DrafterDesc), ctypes.POINTER(ctypes.c_size_t)]
+        l.owl_drafter_cell.restype = ctypes.c_int
+        l.owl_drafter_cell.argtypes = [ctypes.POINTER(DrafterDesc)] + [vp] * 14 + [ctypes.c_size_t, vp, vp]
+        l.owl_drafter_cell_phases.restype = ctypes.c_int
+        l.owl_drafter_cell_phases.argtypes = [ctypes.POINTER(DrafterDesc)] + [vp] * 14 + [ctypes.c_size_t, vp, vp, i32]
+        l.owl_drafter_alpha.restype = ctypes.c_int
+        l.owl_drafter_alpha.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_float)]
         l.owl_prepare_spec_tree.restype = ctypes.c_int
         l.owl_prepare_spec_tree.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]
         l.owl_accept_greedy.restype = ctypes.c_int
@@ -277,3 +297,37 @@ def owl_mfma_probe(src, iters: int, sink, n_workgroups: int, stream: Optional[in
     rc = lib().owl_mfma_probe(_ptr(src), src.numel() * src.element_size(), iters, _ptr(sink), n_workgroups,
                               _stream() if stream is None else stream)
     _check(rc, "owl_mfma_probe")
+
+
+def owl_drafter_alpha(max_depth: int, d: int) -> float:
+    a = ctypes.c_float(0.0)
+    _check(lib().owl_drafter_alpha(max_depth, d, ctypes.byref(a)), "owl_drafter_alpha")
+    return float(a.value)
+
+
+def owl_drafter_cell_workspace_size(desc: DrafterDesc) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().owl_drafter_cell_workspace_size(ctypes.byref(desc), ctypes.byref(n)),
+           "owl_drafter_cell_workspace_size")
+    return int(n.value)
+
+
+def owl_drafter_cell_phases(desc: DrafterDesc, h, z, tokens, parent_row, w, emb, gamma_c, beta_c, gamma_z, beta_z,
+                            h_out, h_out_f32, z_out, workspace, dev_status=None, stream: Optional[int] = None,
+                            phases: int = OWL_DRAFTER_ALL) -> None:
+    rc = lib().owl_drafter_cell_phases(ctypes.byref(desc), _ptr(h), _ptr(z), _ptr(tokens), _ptr(parent_row),
+                                       _ptr(w), _ptr(emb), _ptr(gamma_c), _ptr(beta_c), _ptr(gamma_z),
+                                       _ptr(beta_z), _ptr(h_out), _ptr(h_out_f32), _ptr(z_out), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                                       _ptr(dev_status), _stream() if stream is None else stream, phases)
+    _check(rc, "owl_drafter_cell_phases")
+
+
+def owl_drafter_cell(desc: DrafterDesc, h, z, tokens, parent_row, w, emb, gamma_c, beta_c, gamma_z, beta_z,
+                     h_out, h_out_f32, z_out, workspace, dev_status=None, stream: Optional[int] = None) -> None:
+    rc = lib().owl_drafter_cell(ctypes.byref(desc), _ptr(h), _ptr(z), _ptr(tokens), _ptr(parent_row),
+                                _ptr(w), _ptr(emb), _ptr(gamma_c), _ptr(beta_c), _ptr(gamma_z),
+                                _ptr(beta_z), _ptr(h_out), _ptr(h_out_f32), _ptr(z_out), _ptr(workspace),
+                                workspace.numel() * workspace.element_size() if workspace is not None else 0,
+                                _ptr(dev_status), _stream() if stream is None else stream)
+    _check(rc, "owl_drafter_cell")

@@ -327,6 +327,76 @@ owl_status owl_commit_kv(const owl_verify_desc *desc, void *k_cache, void *v_cac
     return OWL_OK;
 }
 
+static owl_status check_drafter(const owl_drafter_desc *d)
+{
+    if (!d) return OWL_ERR_INVALID_ARG;
+    if (d->d_in < 1 || d->d < 1 || d->n_states < 1 || d->n_rows < 1 || d->vocab < 1) return OWL_ERR_INVALID_ARG;
+    if (!(d->eps >= 0.f) || d->alpha != d->alpha) return OWL_ERR_INVALID_ARG;
+    if (d->n_states > 64 || d->n_rows > 64) return OWL_ERR_TOO_MANY_DRAFT;
+    if (d->dtype != OWL_BF16 && d->dtype != OWL_F16) return OWL_ERR_UNSUPPORTED;
+    if (d->d_in % 32 != 0 || d->d % 16 != 0 || d->d > 16384 || d->d_in > (1 << 20)) return OWL_ERR_UNSUPPORTED;
+    return OWL_OK;
+}
+
+owl_status owl_drafter_cell_workspace_size(const owl_drafter_desc *desc, size_t *bytes)
+{
+    owl_status st = check_drafter(desc);
+    if (st != OWL_OK) return st;
+    if (!bytes) return OWL_ERR_INVALID_ARG;
+    *bytes = (size_t)desc->n_states * 4 * desc->d * sizeof(float);
+    return OWL_OK;
+}
+
+owl_status owl_drafter_cell_phases(const owl_drafter_desc *desc, const void *h, const float *z,
+                                   const int32_t *tokens, const int32_t *parent_row, const void *w,
+                                   const void *emb, const float *gamma_c, const float *beta_c,
+                                   const float *gamma_z, const float *beta_z, void *h_out, float *h_out_f32,
+                                   float *z_out, void *workspace, size_t workspace_bytes, uint32_t *dev_status,
+                                   void *stream, int32_t phases)
+{
+    owl_status st = check_drafter(desc);
+    if (st != OWL_OK) return st;
+    if (!h || !z || !tokens || !w || !emb || !z_out) return OWL_ERR_INVALID_ARG;
+    if (phases < 1 || phases > OWL_DRAFTER_ALL) return OWL_ERR_INVALID_ARG;
+    if (!parent_row && desc->n_rows != desc->n_states) return OWL_ERR_INVALID_ARG;
+    if (misaligned(h, 16) || misaligned(w, 16) || misaligned(emb, 2) || misaligned(z, 4) || misaligned(z_out, 4) ||
+        misaligned(workspace, 16) || (h_out && misaligned(h_out, 2)) || (h_out_f32 && misaligned(h_out_f32, 4)))
+        return OWL_ERR_INVALID_ARG;
+    size_t need = 0;
+    owl_drafter_cell_workspace_size(desc, &need);
+    if (!workspace || workspace_bytes < need) return OWL_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float *proj = static_cast<float *>(workspace);
+    if (phases & OWL_DRAFTER_PROJ)
+        if (launch_drafter_proj(desc->dtype, h, w, proj, desc->n_states, desc->d_in, desc->d, s) != hipSuccess)
+            return OWL_ERR_HIP;
+    if (phases & OWL_DRAFTER_GATES)
+        if (launch_drafter_gates(desc->dtype, proj, z, tokens, parent_row, emb, gamma_c, beta_c, gamma_z, beta_z,
+                                 h_out, h_out_f32, z_out, desc->n_states, desc->n_rows, desc->d, desc->vocab,
+                                 desc->alpha, desc->eps, dev_status, s) != hipSuccess)
+            return OWL_ERR_HIP;
+    return OWL_OK;
+}
+
+owl_status owl_drafter_cell(const owl_drafter_desc *desc, const void *h, const float *z, const int32_t *tokens,
+                            const int32_t *parent_row, const void *w, const void *emb, const float *gamma_c,
+                            const float *beta_c, const float *gamma_z, const float *beta_z, void *h_out,
+                            float *h_out_f32, float *z_out, void *workspace, size_t workspace_bytes,
+                            uint32_t *dev_status, void *stream)
+{
+    return owl_drafter_cell_phases(desc, h, z, tokens, parent_row, w, emb, gamma_c, beta_c, gamma_z, beta_z, h_out,
+                                   h_out_f32, z_out, workspace, workspace_bytes, dev_status, stream,
+                                   OWL_DRAFTER_ALL);
+}
+
+owl_status owl_drafter_alpha(int32_t max_depth, int32_t d, float *alpha_host)
+{
+    if (max_depth < 1 || d < 1 || !alpha_host) return OWL_ERR_INVALID_ARG;
+    const double a0 = exp2(-1.0 / (2.0 * (double)max_depth));
+    *alpha_host = (float)(2.0 * a0 / ((1.0 - a0 * a0) * (double)d));
+    return OWL_OK;
+}
+
 owl_status owl_build_tree_mask_host(const int32_t *parent, int32_t n_draft, uint64_t *anc,
                                     int32_t *depth)
 {

@@ -1,0 +1,302 @@
+// One step of the drafter's recurrent cell (Sec. 3.2.1, Eq. 1-8 of the paper):
+//     e   = E[t]                                   s^m = W^m h + alpha e,  m in {f, i, o, c}
+//     g^m = sigmoid(s^m), m in {f, i, o}           c   = f(s^c) g^i
+//     z'  = z g^f + c                              h'  = f(z') g^o
+// with f = layer normalisation over the d channels followed by GeLU.
+//
+// Two kernels.  The projection W^m h reads every weight exactly once (4 d d_in
+// elements, 1.2 GB for the paper's d = 12288 with a square W) against at most
+// 64 state rows: a streaming read of HBM with a thin contraction on the side,
+// done with MFMA only because 64 rows x 4 d x d_in multiply-adds per step are
+// beyond the vector ALUs at that rate.  Weights go from global memory straight
+// into the MFMA operand registers: no element is used twice, so there is
+// nothing to stage in LDS.  The gate kernel then needs whole-row statistics
+// twice (of s^c and of z'), which is why it is a launch of its own: one
+// workgroup per row keeps the row on chip and reduces across the workgroup.
+#include "owl_device.h"
+
+namespace owl {
+
+typedef float d_f32x4 __attribute__((ext_vector_type(4)));
+typedef int d_i32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 d_bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 d_f16x8 __attribute__((ext_vector_type(8)));
+
+template <bool kF16>
+__device__ __forceinline__ d_f32x4 mfma16(d_i32x4 a, d_i32x4 b, d_f32x4 c)
+{
+    if constexpr (kF16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(d_f16x8, a),
+                                                      __builtin_bit_cast(d_f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(d_bf16x8, a),
+                                                       __builtin_bit_cast(d_bf16x8, b), c, 0, 0, 0);
+}
+
+// ---------------------------------------------------------------------------
+// Projection.  The four W^m, each [d][d_in] (one output channel's weights
+// contiguous), are one matrix of 4d rows.  A workgroup of four wavefronts owns
+// 64 consecutive rows (four 16-row MFMA tiles); every wavefront works on all
+// four tiles, so that a fragment of h is loaded once per four weight fragments,
+// and the wavefronts split the contraction dimension: wavefront w takes the
+// k-blocks w, w + 4, ... of 128 elements, which makes the workgroup's reads of a
+// weight row contiguous (1 KB per row and round).  In MFMA terms A = h (rows =
+// states), B = W^T (columns = weight rows): lane l supplies the 8 consecutive k
+// values of group l / 16 for state row / weight row l % 16, 16 bytes straight
+// from memory.  The four partial sums meet in LDS and are added in a fixed order.
+//     s [P][4d] fp32, s[p][m * d + j] = (W^m h_p)[j]
+// ---------------------------------------------------------------------------
+constexpr int kProjWaves = 4;
+constexpr int kProjTiles = 4;     // 16-row weight tiles per workgroup
+constexpr int kProjUnroll = 4;    // k-steps of 32 per wavefront and round
+
+template <bool kF16, int PT>
+__global__ void __launch_bounds__(kProjWaves * 64) drafter_proj_kernel(const uint16_t *__restrict__ h,
+                                                                       const uint16_t *__restrict__ w,
+                                                                       float *__restrict__ s, int P, int d_in,
+                                                                       int n_rows)
+{
+    __shared__ d_f32x4 red[kProjWaves][kProjTiles][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, kg = lane >> 4;
+    const int n_tiles = n_rows / 16;
+    const int tile0 = blockIdx.x * kProjTiles;
+
+    // A tile past the end re-reads the last tile (in bounds); its sums are not stored.
+    const uint16_t *wp[kProjTiles];
+#pragma unroll
+    for (int nb = 0; nb < kProjTiles; ++nb) {
+        const int t = min(tile0 + nb, n_tiles - 1);
+        wp[nb] = w + (int64_t)(t * 16 + n) * d_in + kg * 8;
+    }
+    // State rows past P read row P - 1 (in bounds) and are not stored either.
+    const uint16_t *hp[PT];
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) hp[pt] = h + (int64_t)min(pt * 16 + n, P - 1) * d_in + kg * 8;
+
+    d_f32x4 acc[PT][kProjTiles];
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+        for (int nb = 0; nb < kProjTiles; ++nb) acc[pt][nb] = d_f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int k_steps = d_in / 32;
+    for (int ks0 = wave * kProjUnroll; ks0 < k_steps; ks0 += kProjWaves * kProjUnroll) {
+        d_i32x4 b[kProjUnroll][kProjTiles], a[kProjUnroll][PT];
+#pragma unroll
+        for (int u = 0; u < kProjUnroll; ++u) {
+            const bool live = ks0 + u < k_steps;            // uniform over the wavefront
+            const int ko = live ? (ks0 + u) * 32 : 0;
+#pragma unroll
+            for (int nb = 0; nb < kProjTiles; ++nb) {
+                b[u][nb] = *reinterpret_cast<const d_i32x4 *>(wp[nb] + ko);
+                if (!live) b[u][nb] = d_i32x4{0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt) a[u][pt] = *reinterpret_cast<const d_i32x4 *>(hp[pt] + ko);
+        }
+#pragma unroll
+        for (int u = 0; u < kProjUnroll; ++u)
+#pragma unroll
+            for (int pt = 0; pt < PT; ++pt)
+#pragma unroll
+                for (int nb = 0; nb < kProjTiles; ++nb) acc[pt][nb] = mfma16<kF16>(a[u][pt], b[u][nb], acc[pt][nb]);
+    }
+
+    // Accumulator layout: lane l holds, for weight row l % 16, the state rows 4 (l / 16) + i.
+    const int t_mine = tile0 + wave;
+#pragma unroll
+    for (int pt = 0; pt < PT; ++pt) {
+        if (pt) __syncthreads();
+#pragma unroll
+        for (int nb = 0; nb < kProjTiles; ++nb) red[wave][nb][lane] = acc[pt][nb];
+        __syncthreads();
+        if (t_mine < n_tiles) {
+            d_f32x4 v = red[0][wave][lane];
+#pragma unroll
+            for (int ww = 1; ww < kProjWaves; ++ww) v += red[ww][wave][lane];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int p = pt * 16 + kg * 4 + i;
+                if (p < P) s[(int64_t)p * n_rows + t_mine * 16 + n] = v[i];
+            }
+        }
+    }
+}
+
+template <bool kF16, int PT>
+static hipError_t launch_proj_pt(const void *h, const void *w, float *s, int P, int d_in, int d, hipStream_t st)
+{
+    const int n_rows = 4 * d, n_tiles = n_rows / 16;
+    const int grid = (n_tiles + kProjTiles - 1) / kProjTiles;
+    hipLaunchKernelGGL((drafter_proj_kernel<kF16, PT>), dim3(grid), dim3(kProjWaves * 64), 0, st,
+                       static_cast<const uint16_t *>(h), static_cast<const uint16_t *>(w), s, P, d_in, n_rows);
+    return hipGetLastError();
+}
+
+template <bool kF16>
+static hipError_t launch_proj_dt(const void *h, const void *w, float *s, int P, int d_in, int d, hipStream_t st)
+{
+    switch ((P + 15) / 16) {
+    case 1: return launch_proj_pt<kF16, 1>(h, w, s, P, d_in, d, st);
+    case 2: return launch_proj_pt<kF16, 2>(h, w, s, P, d_in, d, st);
+    case 3: return launch_proj_pt<kF16, 3>(h, w, s, P, d_in, d, st);
+    default: return launch_proj_pt<kF16, 4>(h, w, s, P, d_in, d, st);
+    }
+}
+
+hipError_t launch_drafter_proj(int dtype, const void *h, const void *w, float *s, int P, int d_in, int d,
+                               hipStream_t st)
+{
+    return dtype == OWL_F16 ? launch_proj_dt<true>(h, w, s, P, d_in, d, st)
+                            : launch_proj_dt<false>(h, w, s, P, d_in, d, st);
+}
+
+// ---------------------------------------------------------------------------
+// Gates and state update: one workgroup of 1024 threads per row of the step,
+// thread t owning the channels t, t + 1024, ...  The mean and the centred sum of
+// squares of the two normalisations are each a reduction over the workgroup;
+// between them the row being normalised (first s^c, then z') waits in LDS, every
+// thread reading back only what it wrote itself.  The gates are formed where they
+// are used, from projections that sit in L2.
+// ---------------------------------------------------------------------------
+constexpr int kCellThreads = 1024;
+
+__device__ __forceinline__ float block_sum(float v, float *scratch)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __syncthreads();                                        // scratch may still be read from the last call
+    if (lane == 0) scratch[wave] = v;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < kCellThreads / 64; ++i) t += scratch[i];   // same order in every thread
+    return t;
+}
+
+__device__ __forceinline__ float sigmoid_f(float x) { return 1.0f / (1.0f + expf(-x)); }
+__device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+
+template <bool kF16> __device__ __forceinline__ float widen16(uint16_t b)
+{
+    if constexpr (kF16) return (float)__builtin_bit_cast(_Float16, b);
+    else return __builtin_bit_cast(float, (uint32_t)b << 16);
+}
+
+template <bool kF16> __device__ __forceinline__ uint16_t narrow16(float x)
+{
+    if constexpr (kF16) {
+        return __builtin_bit_cast(uint16_t, (_Float16)x);   // round to nearest even in hardware
+    } else {
+        uint32_t u = __builtin_bit_cast(uint32_t, x);
+        if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);   // NaN stays NaN
+        u += 0x7fffu + ((u >> 16) & 1u);                    // round to nearest even
+        return (uint16_t)(u >> 16);
+    }
+}
+
+template <bool kF16>
+__global__ void __launch_bounds__(kCellThreads) drafter_gates_kernel(
+    const float *__restrict__ s, const float *__restrict__ z, const int32_t *__restrict__ tokens,
+    const int32_t *__restrict__ parent_row, const uint16_t *__restrict__ emb, const float *__restrict__ gamma_c,
+    const float *__restrict__ beta_c, const float *__restrict__ gamma_z, const float *__restrict__ beta_z,
+    uint16_t *__restrict__ h_out, float *__restrict__ h_out_f32, float *__restrict__ z_out, int P, int d,
+    int vocab, float alpha, float eps, uint32_t *status)
+{
+    extern __shared__ float lds[];
+    float *scratch = lds;                                   // kCellThreads / 64 partial sums
+    float *row = lds + kCellThreads / 64;                   // d floats
+    const int r = blockIdx.x, tid = threadIdx.x;
+    int p = parent_row ? parent_row[r] : r;
+    if (p < 0 || p >= P) {
+        if (tid == 0) flag_status(status, OWL_DEV_BAD_ROW);
+        p = 0;
+    }
+    int tok = tokens[r];
+    if (tok < 0 || tok >= vocab) {
+        if (tid == 0) flag_status(status, OWL_DEV_BAD_TOKEN);
+        tok = 0;
+        alpha = 0.f;                                        // e = 0 for this row
+    }
+    const float *sp = s + (int64_t)p * 4 * d;
+    const float *zp = z + (int64_t)p * d;
+    const uint16_t *ep = emb + (int64_t)tok * d;
+    const float inv_d = 1.0f / (float)d;
+
+    float sum = 0.f;
+    for (int j = tid; j < d; j += kCellThreads) {
+        const float v = sp[3 * d + j] + alpha * widen16<kF16>(ep[j]);
+        row[j] = v;
+        sum += v;
+    }
+    const float mean_c = block_sum(sum, scratch) * inv_d;
+    float sq = 0.f;
+    for (int j = tid; j < d; j += kCellThreads) {
+        const float v = row[j] - mean_c;
+        row[j] = v;
+        sq += v * v;
+    }
+    const float rstd_c = 1.0f / sqrtf(block_sum(sq, scratch) * inv_d + eps);
+    sum = 0.f;
+    for (int j = tid; j < d; j += kCellThreads) {
+        const float ae = alpha * widen16<kF16>(ep[j]);
+        float y = row[j] * rstd_c;
+        if (gamma_c) y *= gamma_c[j];
+        if (beta_c) y += beta_c[j];
+        const float zn = zp[j] * sigmoid_f(sp[j] + ae) + gelu_f(y) * sigmoid_f(sp[d + j] + ae);
+        z_out[(int64_t)r * d + j] = zn;
+        row[j] = zn;                                        // from here on: the new cell state
+        sum += zn;
+    }
+    const float mean_z = block_sum(sum, scratch) * inv_d;
+    sq = 0.f;
+    for (int j = tid; j < d; j += kCellThreads) {
+        const float v = row[j] - mean_z;
+        row[j] = v;
+        sq += v * v;
+    }
+    const float rstd_z = 1.0f / sqrtf(block_sum(sq, scratch) * inv_d + eps);
+    for (int j = tid; j < d; j += kCellThreads) {
+        const float ae = alpha * widen16<kF16>(ep[j]);
+        float y = row[j] * rstd_z;
+        if (gamma_z) y *= gamma_z[j];
+        if (beta_z) y += beta_z[j];
+        const float hn = gelu_f(y) * sigmoid_f(sp[2 * d + j] + ae);
+        if (h_out) h_out[(int64_t)r * d + j] = narrow16<kF16>(hn);
+        if (h_out_f32) h_out_f32[(int64_t)r * d + j] = hn;
+    }
+}
+
+template <bool kF16>
+static hipError_t launch_gates_dt(const float *s, const float *z, const int32_t *tokens, const int32_t *parent_row,
+                                  const void *emb, const float *gamma_c, const float *beta_c, const float *gamma_z,
+                                  const float *beta_z, void *h_out, float *h_out_f32, float *z_out, int P, int M,
+                                  int d, int vocab, float alpha, float eps, uint32_t *status, hipStream_t st)
+{
+    const size_t lds = ((size_t)d + kCellThreads / 64) * sizeof(float);
+    if (lds > 64 * 1024) {                                  // beyond the default cap of dynamic LDS
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&drafter_gates_kernel<kF16>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(drafter_gates_kernel<kF16>, dim3(M), dim3(kCellThreads), lds, st, s, z, tokens, parent_row,
+                       static_cast<const uint16_t *>(emb), gamma_c, beta_c, gamma_z, beta_z,
+                       static_cast<uint16_t *>(h_out), h_out_f32, z_out, P, d, vocab, alpha, eps, status);
+    return hipGetLastError();
+}
+
+hipError_t launch_drafter_gates(int dtype, const float *s, const float *z, const int32_t *tokens,
+                                const int32_t *parent_row, const void *emb, const float *gamma_c,
+                                const float *beta_c, const float *gamma_z, const float *beta_z, void *h_out,
+                                float *h_out_f32, float *z_out, int P, int M, int d, int vocab, float alpha,
+                                float eps, uint32_t *status, hipStream_t st)
+{
+    return dtype == OWL_F16 ? launch_gates_dt<true>(s, z, tokens, parent_row, emb, gamma_c, beta_c, gamma_z, beta_z,
+                                                    h_out, h_out_f32, z_out, P, M, d, vocab, alpha, eps, status, st)
+                            : launch_gates_dt<false>(s, z, tokens, parent_row, emb, gamma_c, beta_c, gamma_z, beta_z,
+                                                     h_out, h_out_f32, z_out, P, M, d, vocab, alpha, eps, status, st);
+}
+
+}  // namespace owl

@@ -57,6 +57,13 @@ hipError_t launch_accept(const int32_t *tokens, const int32_t *parent, const int
 hipError_t launch_commit(const owl_verify_desc &d, void *k_cache, void *v_cache, const int32_t *page_table,
                          const int32_t *ctx_lens, const int32_t *accepted, const int32_t *n_accept,
                          int32_t *new_ctx_lens, uint32_t *status, hipStream_t s);
+hipError_t launch_drafter_proj(int dtype, const void *h, const void *w, float *s, int P, int d_in, int d,
+                               hipStream_t st);
+hipError_t launch_drafter_gates(int dtype, const float *s, const float *z, const int32_t *tokens,
+                                const int32_t *parent_row, const void *emb, const float *gamma_c,
+                                const float *beta_c, const float *gamma_z, const float *beta_z, void *h_out,
+                                float *h_out_f32, float *z_out, int P, int M, int d, int vocab, float alpha,
+                                float eps, uint32_t *status, hipStream_t st);
 hipError_t launch_tree_mask(const int32_t *parent, int B, int N, uint64_t *anc, int32_t *depth,
                             uint32_t *status, hipStream_t s);
 hipError_t launch_gather(const owl_verify_desc &d, const void *cache, const int32_t *page_table,

@@ -64,3 +64,43 @@ class VerifyStep:
     def dev_status(self) -> int:
         torch.cuda.synchronize(self.device)
         return int(self.status.item())
+
+
+class DrafterStep:
+    """Device residency for one step of the drafter's cell on a ``workloads.DrafterCase``."""
+
+    def __init__(self, case: W.DrafterCase, alpha: float, device: str = "cuda:0"):
+        self.case = case
+        self.device = torch.device(device)
+        up = lambda a: None if a is None else _to_dev(np.ascontiguousarray(a), self.device)
+        self.h, self.z, self.w, self.emb = up(case.h), up(case.z), up(case.W), up(case.E)
+        self.tokens, self.parent_row = up(case.tokens), up(case.parent_row)
+        self.gamma_c, self.beta_c = up(case.gamma_c), up(case.beta_c)
+        self.gamma_z, self.beta_z = up(case.gamma_z), up(case.beta_z)
+        self.h_out = torch.zeros((case.M, case.d), dtype=torch.int16, device=self.device)
+        self.h_out_f32 = torch.zeros((case.M, case.d), dtype=torch.float32, device=self.device)
+        self.z_out = torch.zeros((case.M, case.d), dtype=torch.float32, device=self.device)
+        self.status = torch.zeros(1, dtype=torch.int32, device=self.device)
+        self.desc = B.DrafterDesc(d_in=case.d_in, d=case.d, n_states=case.P, n_rows=case.M, vocab=case.vocab,
+                                  dtype=case.dtype, alpha=alpha, eps=case.eps)
+        self.workspace = torch.empty(B.owl_drafter_cell_workspace_size(self.desc), dtype=torch.uint8,
+                                     device=self.device)
+
+    def run(self, w=None, stream: Optional[int] = None, phases: int = B.OWL_DRAFTER_ALL) -> None:
+        """``w`` lets a caller rotate through several resident copies of the weights."""
+        args = (self.desc, self.h, self.z, self.tokens, self.parent_row, self.w if w is None else w, self.emb,
+                self.gamma_c, self.beta_c, self.gamma_z, self.beta_z, self.h_out, self.h_out_f32, self.z_out,
+                self.workspace, self.status)
+        if phases == B.OWL_DRAFTER_ALL:
+            B.owl_drafter_cell(*args, stream=stream)
+        else:
+            B.owl_drafter_cell_phases(*args, stream=stream, phases=phases)
+
+    def result(self):
+        """(h' float32, h' in the storage type as uint16 bits, z' float32) as numpy arrays."""
+        torch.cuda.synchronize(self.device)
+        return (self.h_out_f32.cpu().numpy(), self.h_out.cpu().numpy().view(np.uint16), self.z_out.cpu().numpy())
+
+    def dev_status(self) -> int:
+        torch.cuda.synchronize(self.device)
+        return int(self.status.item())

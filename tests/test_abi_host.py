@@ -171,3 +171,60 @@ def test_mfma_probe_rejects_before_launch():
     assert lib.owl_mfma_probe(A, 4100, 10, A, 4, None) == B.OWL_ERR_INVALID_ARG       # not a multiple of 16
     assert lib.owl_mfma_probe(A, 4096, 0, A, 4, None) == B.OWL_ERR_INVALID_ARG
     assert lib.owl_mfma_probe(A + 4, 4096, 10, A, 4, None) == B.OWL_ERR_INVALID_ARG
+
+
+# --------------------------------------------------------------------------- drafter cell
+def _drafter(**over):
+    kw = dict(d_in=12288, d=12288, n_states=10, n_rows=10, vocab=128256, dtype=B.OWL_BF16, alpha=0.002, eps=1e-5)
+    kw.update(over)
+    return B.DrafterDesc(**kw)
+
+
+def test_drafter_struct_and_workspace():
+    assert ctypes.sizeof(B.DrafterDesc) == 8 * 4
+    assert B.owl_drafter_cell_workspace_size(_drafter()) == 10 * 4 * 12288 * 4
+
+
+@pytest.mark.parametrize("over,code", [
+    (dict(d_in=0), B.OWL_ERR_INVALID_ARG),
+    (dict(d_in=100), B.OWL_ERR_UNSUPPORTED),
+    (dict(d=24), B.OWL_ERR_UNSUPPORTED),
+    (dict(d=16400), B.OWL_ERR_UNSUPPORTED),
+    (dict(n_states=65), B.OWL_ERR_TOO_MANY_DRAFT),
+    (dict(n_rows=0), B.OWL_ERR_INVALID_ARG),
+    (dict(dtype=B.OWL_F32), B.OWL_ERR_UNSUPPORTED),
+    (dict(eps=-1.0), B.OWL_ERR_INVALID_ARG),
+    (dict(alpha=float("nan")), B.OWL_ERR_INVALID_ARG),
+    (dict(vocab=0), B.OWL_ERR_INVALID_ARG),
+])
+def test_drafter_bad_descriptors_are_rejected(over, code):
+    with pytest.raises(B.OwlError) as e:
+        B.owl_drafter_cell_workspace_size(_drafter(**over))
+    assert e.value.code == code
+
+
+def test_drafter_cell_rejects_before_launch():
+    lib = B.lib()
+    d = _drafter()
+    fake = 0x1000                                       # never dereferenced: every call below fails its checks
+
+    def call(desc, h=fake, z=fake, tokens=fake, parent=fake, w=fake, emb=fake, z_out=fake, ws=fake,
+             ws_bytes=1 << 30, phases=3):
+        return lib.owl_drafter_cell_phases(ctypes.byref(desc), h, z, tokens, parent, w, emb, None, None, None, None,
+                                           None, None, z_out, ws, ws_bytes, None, None, phases)
+    assert call(d, h=None) == B.OWL_ERR_INVALID_ARG
+    assert call(d, w=None) == B.OWL_ERR_INVALID_ARG
+    assert call(d, z_out=None) == B.OWL_ERR_INVALID_ARG
+    assert call(d, w=fake + 2) == B.OWL_ERR_INVALID_ARG
+    assert call(d, phases=0) == B.OWL_ERR_INVALID_ARG
+    assert call(d, phases=4) == B.OWL_ERR_INVALID_ARG
+    assert call(d, ws=None) == B.OWL_ERR_WORKSPACE
+    assert call(d, ws_bytes=100) == B.OWL_ERR_WORKSPACE
+    assert call(_drafter(n_rows=7), parent=None) == B.OWL_ERR_INVALID_ARG   # identity needs n_rows == n_states
+
+
+def test_drafter_alpha_host():
+    import math
+    assert B.owl_drafter_alpha(1, 8) == pytest.approx(2 * math.sqrt(2) / 8, rel=1e-6)
+    with pytest.raises(B.OwlError):
+        B.owl_drafter_alpha(0, 8)
