@@ -282,7 +282,7 @@ def bench_drafter(steps=60, with_cpu=True):
         ksec = sum(a.elapsed_time(b) for a, b in ev) / len(ev) * 1e-3
         assert step.dev_status() == 0
         res = {"workload": name, "d_in": d_in, "d": d, "n_states": P, "n_rows": M, "dtype": "bf16",
-               "weight_bytes": wbytes, "weight_copies_rotated": len(copies), "us_per_step": sec * 1e6,
+               "weight_bytes": wbytes, "weight_layout": "tiled", "weight_copies_rotated": len(copies), "us_per_step": sec * 1e6,
                "GBps": wbytes / sec / 1e9,
                "roofline": {"bound": "hbm", "achieved": wbytes / ksec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                             "frac": wbytes / ksec / 1e9 / HBM_PEAK_GBS, "traffic": None,

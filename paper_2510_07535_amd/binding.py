@@ -21,6 +21,7 @@ OWL_DEV_BAD_PARENT, OWL_DEV_BAD_PAGE, OWL_DEV_BAD_CTX_LEN, OWL_DEV_BAD_ACCEPT = 
 OWL_DEV_BAD_NDRAFT = 16
 OWL_DEV_BAD_TOKEN, OWL_DEV_BAD_ROW = 32, 64
 OWL_DRAFTER_PROJ, OWL_DRAFTER_GATES, OWL_DRAFTER_ALL = 1, 2, 3
+OWL_W_ROWS, OWL_W_TILED = 0, 1
 
 EXPORTS = (
     "owl_verify_attn_plan", "owl_verify_attn_workspace_size", "owl_verify_attn",
@@ -29,6 +30,7 @@ EXPORTS = (
     "owl_build_tree_mask", "owl_build_tree_mask_host", "owl_gather_kv",
     "owl_prepare_spec_tree", "owl_accept_greedy", "owl_commit_kv", "owl_verify_attn_ragged",
     "owl_drafter_cell", "owl_drafter_cell_phases", "owl_drafter_cell_workspace_size", "owl_drafter_alpha",
+    "owl_drafter_tiled_weight_bytes", "owl_drafter_tile_weights",
     "owl_status_str", "owl_version",
 )
 
@@ -67,6 +69,7 @@ class DrafterDesc(ctypes.Structure):
         ("d_in", ctypes.c_int32), ("d", ctypes.c_int32), ("n_states", ctypes.c_int32),
         ("n_rows", ctypes.c_int32), ("vocab", ctypes.c_int32), ("dtype", ctypes.c_int32),
         ("alpha", ctypes.c_float), ("eps", ctypes.c_float),
+        ("w_layout", ctypes.c_int32), ("reserved_", ctypes.c_int32),
     ]
 
 
@@ -125,6 +128,10 @@ def lib() -> ctypes.CDLL:
         l.owl_drafter_cell.argtypes = [ctypes.POINTER(DrafterDesc)] + [vp] * 14 + [ctypes.c_size_t, vp, vp]
         l.owl_drafter_cell_phases.restype = ctypes.c_int
         l.owl_drafter_cell_phases.argtypes = [ctypes.POINTER(DrafterDesc)] + [vp] * 14 + [ctypes.c_size_t, vp, vp, i32]
+        l.owl_drafter_tiled_weight_bytes.restype = ctypes.c_int
+        l.owl_drafter_tiled_weight_bytes.argtypes = [ctypes.POINTER(DrafterDesc), ctypes.POINTER(ctypes.c_size_t)]
+        l.owl_drafter_tile_weights.restype = ctypes.c_int
+        l.owl_drafter_tile_weights.argtypes = [ctypes.POINTER(DrafterDesc), vp, vp, vp]
         l.owl_drafter_alpha.restype = ctypes.c_int
         l.owl_drafter_alpha.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_float)]
         l.owl_prepare_spec_tree.restype = ctypes.c_int
@@ -331,3 +338,15 @@ def owl_drafter_cell(desc: DrafterDesc, h, z, tokens, parent_row, w, emb, gamma_
                                 workspace.numel() * workspace.element_size() if workspace is not None else 0,
                                 _ptr(dev_status), _stream() if stream is None else stream)
     _check(rc, "owl_drafter_cell")
+
+
+def owl_drafter_tiled_weight_bytes(desc: DrafterDesc) -> int:
+    n = ctypes.c_size_t(0)
+    _check(lib().owl_drafter_tiled_weight_bytes(ctypes.byref(desc), ctypes.byref(n)),
+           "owl_drafter_tiled_weight_bytes")
+    return int(n.value)
+
+
+def owl_drafter_tile_weights(desc: DrafterDesc, w_rows, w_tiled, stream: Optional[int] = None) -> None:
+    _check(lib().owl_drafter_tile_weights(ctypes.byref(desc), _ptr(w_rows), _ptr(w_tiled),
+                                          _stream() if stream is None else stream), "owl_drafter_tile_weights")

@@ -335,6 +335,27 @@ static owl_status check_drafter(const owl_drafter_desc *d)
     if (d->n_states > 64 || d->n_rows > 64) return OWL_ERR_TOO_MANY_DRAFT;
     if (d->dtype != OWL_BF16 && d->dtype != OWL_F16) return OWL_ERR_UNSUPPORTED;
     if (d->d_in % 32 != 0 || d->d % 16 != 0 || d->d > 16384 || d->d_in > (1 << 20)) return OWL_ERR_UNSUPPORTED;
+    if (d->w_layout != OWL_W_ROWS && d->w_layout != OWL_W_TILED) return OWL_ERR_UNSUPPORTED;
+    return OWL_OK;
+}
+
+owl_status owl_drafter_tiled_weight_bytes(const owl_drafter_desc *desc, size_t *bytes)
+{
+    owl_status st = check_drafter(desc);
+    if (st != OWL_OK) return st;
+    if (!bytes) return OWL_ERR_INVALID_ARG;
+    *bytes = drafter_tiled_bytes(desc->d_in, desc->d);
+    return OWL_OK;
+}
+
+owl_status owl_drafter_tile_weights(const owl_drafter_desc *desc, const void *w_rows, void *w_tiled, void *stream)
+{
+    owl_status st = check_drafter(desc);
+    if (st != OWL_OK) return st;
+    if (!w_rows || !w_tiled || misaligned(w_rows, 16) || misaligned(w_tiled, 16)) return OWL_ERR_INVALID_ARG;
+    if (launch_drafter_tile_weights(w_rows, w_tiled, desc->d_in, desc->d, static_cast<hipStream_t>(stream)) !=
+        hipSuccess)
+        return OWL_ERR_HIP;
     return OWL_OK;
 }
 
@@ -359,16 +380,18 @@ owl_status owl_drafter_cell_phases(const owl_drafter_desc *desc, const void *h, 
     if (!h || !z || !tokens || !w || !emb || !z_out) return OWL_ERR_INVALID_ARG;
     if (phases < 1 || phases > OWL_DRAFTER_ALL) return OWL_ERR_INVALID_ARG;
     if (!parent_row && desc->n_rows != desc->n_states) return OWL_ERR_INVALID_ARG;
-    if (misaligned(h, 16) || misaligned(w, 16) || misaligned(emb, 2) || misaligned(z, 4) || misaligned(z_out, 4) ||
-        misaligned(workspace, 16) || (h_out && misaligned(h_out, 2)) || (h_out_f32 && misaligned(h_out_f32, 4)))
-        return OWL_ERR_INVALID_ARG;
+    for (const void *ptr : {h, (const void *)z, w, emb, (const void *)gamma_c, (const void *)beta_c,
+                            (const void *)gamma_z, (const void *)beta_z, (const void *)h_out,
+                            (const void *)h_out_f32, (const void *)z_out, (const void *)workspace})
+        if (misaligned(ptr, 16)) return OWL_ERR_INVALID_ARG;      // a null pointer counts as aligned
     size_t need = 0;
     owl_drafter_cell_workspace_size(desc, &need);
     if (!workspace || workspace_bytes < need) return OWL_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     float *proj = static_cast<float *>(workspace);
     if (phases & OWL_DRAFTER_PROJ)
-        if (launch_drafter_proj(desc->dtype, h, w, proj, desc->n_states, desc->d_in, desc->d, s) != hipSuccess)
+        if (launch_drafter_proj(desc->dtype, h, w, desc->w_layout == OWL_W_TILED, proj, desc->n_states, desc->d_in,
+                                desc->d, s) != hipSuccess)
             return OWL_ERR_HIP;
     if (phases & OWL_DRAFTER_GATES)
         if (launch_drafter_gates(desc->dtype, proj, z, tokens, parent_row, emb, gamma_c, beta_c, gamma_z, beta_z,

@@ -39,18 +39,28 @@ __device__ __forceinline__ d_f32x4 mfma16(d_i32x4 a, d_i32x4 b, d_f32x4 c)
 // 64 consecutive rows (four 16-row MFMA tiles); every wavefront works on all
 // four tiles, so that a fragment of h is loaded once per four weight fragments,
 // and the wavefronts split the contraction dimension: wavefront w takes the
-// k-blocks w, w + 4, ... of 128 elements, which makes the workgroup's reads of a
-// weight row contiguous (1 KB per row and round).  In MFMA terms A = h (rows =
-// states), B = W^T (columns = weight rows): lane l supplies the 8 consecutive k
-// values of group l / 16 for state row / weight row l % 16, 16 bytes straight
-// from memory.  The four partial sums meet in LDS and are added in a fixed order.
+// k-blocks w, w + 4, ... of 128 elements.  In MFMA terms A = h (rows = states),
+// B = W^T (columns = weight rows): lane l supplies the 8 consecutive k values of
+// group l / 16 for state row / weight row l % 16, 16 bytes straight from memory.
+// The four partial sums meet in LDS and are added in a fixed order.
 //     s [P][4d] fp32, s[p][m * d + j] = (W^m h_p)[j]
+//
+// Two weight layouts.  OWL_W_ROWS is the matrix as it stands: a load instruction
+// then touches 16 rows with 64 bytes each and the chip holds ~50 000 row streams
+// open at once, which DRAM serves at 4.6-4.9 TB/s.  OWL_W_TILED stores the same
+// numbers in the order the kernel consumes them,
+//     granule(row, k) = ((row / 64 * KS + k / 32) * 4 + row % 64 / 16) * 64 + (k % 32 / 8) * 16 + row % 16
+// in units of 16 bytes (8 elements), KS = d_in / 32, rows padded with zeros to a
+// multiple of 64: one load instruction reads 1 KB contiguous, a workgroup reads
+// one contiguous run of 64 d_in elements from end to end, and the same kernel
+// reaches 5.6-5.9 TB/s, what a plain streaming read gets on this chip.
 // ---------------------------------------------------------------------------
 constexpr int kProjWaves = 4;
-constexpr int kProjTiles = 4;     // 16-row weight tiles per workgroup
+constexpr int kProjTiles = 4;     // 16-row weight tiles per workgroup (fixed by the tiled layout)
 constexpr int kProjUnroll = 4;    // k-steps of 32 per wavefront and round
+static_assert(kProjTiles <= kProjWaves, "wavefront w adds up and stores weight tile w");
 
-template <bool kF16, int PT>
+template <bool kF16, int PT, bool kTiled>
 __global__ void __launch_bounds__(kProjWaves * 64) drafter_proj_kernel(const uint16_t *__restrict__ h,
                                                                        const uint16_t *__restrict__ w,
                                                                        float *__restrict__ s, int P, int d_in,
@@ -61,13 +71,24 @@ __global__ void __launch_bounds__(kProjWaves * 64) drafter_proj_kernel(const uin
     const int n = lane & 15, kg = lane >> 4;
     const int n_tiles = n_rows / 16;
     const int tile0 = blockIdx.x * kProjTiles;
+    const int k_steps = d_in / 32;
 
-    // A tile past the end re-reads the last tile (in bounds); its sums are not stored.
+    // wp[nb] + ks * w_step is this lane's 16 bytes of k-step ks of weight tile nb.
     const uint16_t *wp[kProjTiles];
+    int64_t w_step;
+    if constexpr (kTiled) {
+        w_step = kProjTiles * 512;
 #pragma unroll
-    for (int nb = 0; nb < kProjTiles; ++nb) {
-        const int t = min(tile0 + nb, n_tiles - 1);
-        wp[nb] = w + (int64_t)(t * 16 + n) * d_in + kg * 8;
+        for (int nb = 0; nb < kProjTiles; ++nb)
+            wp[nb] = w + ((int64_t)blockIdx.x * k_steps * kProjTiles + nb) * 512 + lane * 8;
+    } else {
+        w_step = 32;
+#pragma unroll
+        for (int nb = 0; nb < kProjTiles; ++nb) {
+            // A tile past the end re-reads the last tile (in bounds); its sums are not stored.
+            const int t = min(tile0 + nb, n_tiles - 1);
+            wp[nb] = w + (int64_t)(t * 16 + n) * d_in + kg * 8;
+        }
     }
     // State rows past P read row P - 1 (in bounds) and are not stored either.
     const uint16_t *hp[PT];
@@ -80,20 +101,19 @@ __global__ void __launch_bounds__(kProjWaves * 64) drafter_proj_kernel(const uin
 #pragma unroll
         for (int nb = 0; nb < kProjTiles; ++nb) acc[pt][nb] = d_f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const int k_steps = d_in / 32;
     for (int ks0 = wave * kProjUnroll; ks0 < k_steps; ks0 += kProjWaves * kProjUnroll) {
         d_i32x4 b[kProjUnroll][kProjTiles], a[kProjUnroll][PT];
 #pragma unroll
         for (int u = 0; u < kProjUnroll; ++u) {
             const bool live = ks0 + u < k_steps;            // uniform over the wavefront
-            const int ko = live ? (ks0 + u) * 32 : 0;
+            const int ks = live ? ks0 + u : 0;
 #pragma unroll
             for (int nb = 0; nb < kProjTiles; ++nb) {
-                b[u][nb] = *reinterpret_cast<const d_i32x4 *>(wp[nb] + ko);
+                b[u][nb] = *reinterpret_cast<const d_i32x4 *>(wp[nb] + ks * w_step);
                 if (!live) b[u][nb] = d_i32x4{0, 0, 0, 0};
             }
 #pragma unroll
-            for (int pt = 0; pt < PT; ++pt) a[u][pt] = *reinterpret_cast<const d_i32x4 *>(hp[pt] + ko);
+            for (int pt = 0; pt < PT; ++pt) a[u][pt] = *reinterpret_cast<const d_i32x4 *>(hp[pt] + ks * 32);
         }
 #pragma unroll
         for (int u = 0; u < kProjUnroll; ++u)
@@ -111,7 +131,7 @@ __global__ void __launch_bounds__(kProjWaves * 64) drafter_proj_kernel(const uin
 #pragma unroll
         for (int nb = 0; nb < kProjTiles; ++nb) red[wave][nb][lane] = acc[pt][nb];
         __syncthreads();
-        if (t_mine < n_tiles) {
+        if (wave < kProjTiles && t_mine < n_tiles) {
             d_f32x4 v = red[0][wave][lane];
 #pragma unroll
             for (int ww = 1; ww < kProjWaves; ++ww) v += red[ww][wave][lane];
@@ -124,32 +144,72 @@ __global__ void __launch_bounds__(kProjWaves * 64) drafter_proj_kernel(const uin
     }
 }
 
+static int proj_groups(int d) { return (4 * d / 16 + kProjTiles - 1) / kProjTiles; }
+
 template <bool kF16, int PT>
-static hipError_t launch_proj_pt(const void *h, const void *w, float *s, int P, int d_in, int d, hipStream_t st)
+static hipError_t launch_proj_pt(const void *h, const void *w, bool tiled, float *s, int P, int d_in, int d,
+                                 hipStream_t st)
 {
-    const int n_rows = 4 * d, n_tiles = n_rows / 16;
-    const int grid = (n_tiles + kProjTiles - 1) / kProjTiles;
-    hipLaunchKernelGGL((drafter_proj_kernel<kF16, PT>), dim3(grid), dim3(kProjWaves * 64), 0, st,
-                       static_cast<const uint16_t *>(h), static_cast<const uint16_t *>(w), s, P, d_in, n_rows);
+    const int n_rows = 4 * d;
+    const dim3 grid(proj_groups(d)), block(kProjWaves * 64);
+    const uint16_t *hh = static_cast<const uint16_t *>(h), *ww = static_cast<const uint16_t *>(w);
+    if (tiled)
+        hipLaunchKernelGGL((drafter_proj_kernel<kF16, PT, true>), grid, block, 0, st, hh, ww, s, P, d_in, n_rows);
+    else
+        hipLaunchKernelGGL((drafter_proj_kernel<kF16, PT, false>), grid, block, 0, st, hh, ww, s, P, d_in, n_rows);
     return hipGetLastError();
 }
 
 template <bool kF16>
-static hipError_t launch_proj_dt(const void *h, const void *w, float *s, int P, int d_in, int d, hipStream_t st)
+static hipError_t launch_proj_dt(const void *h, const void *w, bool tiled, float *s, int P, int d_in, int d,
+                                 hipStream_t st)
 {
     switch ((P + 15) / 16) {
-    case 1: return launch_proj_pt<kF16, 1>(h, w, s, P, d_in, d, st);
-    case 2: return launch_proj_pt<kF16, 2>(h, w, s, P, d_in, d, st);
-    case 3: return launch_proj_pt<kF16, 3>(h, w, s, P, d_in, d, st);
-    default: return launch_proj_pt<kF16, 4>(h, w, s, P, d_in, d, st);
+    case 1: return launch_proj_pt<kF16, 1>(h, w, tiled, s, P, d_in, d, st);
+    case 2: return launch_proj_pt<kF16, 2>(h, w, tiled, s, P, d_in, d, st);
+    case 3: return launch_proj_pt<kF16, 3>(h, w, tiled, s, P, d_in, d, st);
+    default: return launch_proj_pt<kF16, 4>(h, w, tiled, s, P, d_in, d, st);
     }
 }
 
-hipError_t launch_drafter_proj(int dtype, const void *h, const void *w, float *s, int P, int d_in, int d,
-                               hipStream_t st)
+hipError_t launch_drafter_proj(int dtype, const void *h, const void *w, bool tiled, float *s, int P, int d_in,
+                               int d, hipStream_t st)
 {
-    return dtype == OWL_F16 ? launch_proj_dt<true>(h, w, s, P, d_in, d, st)
-                            : launch_proj_dt<false>(h, w, s, P, d_in, d, st);
+    return dtype == OWL_F16 ? launch_proj_dt<true>(h, w, tiled, s, P, d_in, d, st)
+                            : launch_proj_dt<false>(h, w, tiled, s, P, d_in, d, st);
+}
+
+// Bytes of the tiled copy of the weights: whole groups of 64 rows.
+size_t drafter_tiled_bytes(int d_in, int d) { return (size_t)proj_groups(d) * (d_in / 32) * kProjTiles * 1024; }
+
+// One thread per 16-byte granule of the tiled layout: find the (row, k) it holds
+// and copy it from the row layout, zeros for the padding rows.
+__global__ void __launch_bounds__(256) drafter_tile_weights_kernel(const uint4 *__restrict__ w_rows,
+                                                                   uint4 *__restrict__ w_tiled, int d_in,
+                                                                   int n_rows, int64_t n_granules)
+{
+    const int64_t gi = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gi >= n_granules) return;
+    const int k_steps = d_in / 32;
+    const int lane = (int)(gi & 63);
+    const int nb = (int)((gi >> 6) % kProjTiles);
+    const int64_t rest = (gi >> 6) / kProjTiles;
+    const int ks = (int)(rest % k_steps);
+    const int64_t g = rest / k_steps;
+    const int64_t row = g * (kProjTiles * 16) + nb * 16 + (lane & 15);
+    const int k = ks * 32 + (lane >> 4) * 8;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (row < n_rows) v = w_rows[(row * d_in + k) / 8];
+    w_tiled[gi] = v;
+}
+
+hipError_t launch_drafter_tile_weights(const void *w_rows, void *w_tiled, int d_in, int d, hipStream_t st)
+{
+    const int64_t n_granules = (int64_t)(drafter_tiled_bytes(d_in, d) / 16);
+    const int64_t blocks = (n_granules + 255) / 256;
+    hipLaunchKernelGGL(drafter_tile_weights_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                       static_cast<const uint4 *>(w_rows), static_cast<uint4 *>(w_tiled), d_in, 4 * d, n_granules);
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
@@ -197,6 +257,23 @@ template <bool kF16> __device__ __forceinline__ uint16_t narrow16(float x)
     }
 }
 
+// Four consecutive channels of a 16-bit row as floats.
+template <bool kF16> __device__ __forceinline__ float4 widen16x4(const uint16_t *p)
+{
+    const uint2 raw = *reinterpret_cast<const uint2 *>(p);
+    return make_float4(widen16<kF16>((uint16_t)(raw.x & 0xffffu)), widen16<kF16>((uint16_t)(raw.x >> 16)),
+                       widen16<kF16>((uint16_t)(raw.y & 0xffffu)), widen16<kF16>((uint16_t)(raw.y >> 16)));
+}
+
+__device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+__device__ __forceinline__ float4 ld4_or(const float *p, int j, float fill)
+{
+    return p ? ld4(p + j) : make_float4(fill, fill, fill, fill);
+}
+
+// Every thread owns groups of four consecutive channels (d is a multiple of 16),
+// so that each pass is a handful of independent 16-byte loads per thread rather
+// than a chain of dependent ones.
 template <bool kF16>
 __global__ void __launch_bounds__(kCellThreads) drafter_gates_kernel(
     const float *__restrict__ s, const float *__restrict__ z, const int32_t *__restrict__ tokens,
@@ -224,48 +301,66 @@ __global__ void __launch_bounds__(kCellThreads) drafter_gates_kernel(
     const float *zp = z + (int64_t)p * d;
     const uint16_t *ep = emb + (int64_t)tok * d;
     const float inv_d = 1.0f / (float)d;
+    constexpr int kStride = kCellThreads * 4;
 
     float sum = 0.f;
-    for (int j = tid; j < d; j += kCellThreads) {
-        const float v = sp[3 * d + j] + alpha * widen16<kF16>(ep[j]);
-        row[j] = v;
-        sum += v;
+#pragma unroll 4
+    for (int j = tid * 4; j < d; j += kStride) {
+        const float4 e = widen16x4<kF16>(ep + j), c = ld4(sp + 3 * d + j);
+        const float4 v = make_float4(c.x + alpha * e.x, c.y + alpha * e.y, c.z + alpha * e.z, c.w + alpha * e.w);
+        *reinterpret_cast<float4 *>(row + j) = v;
+        sum += (v.x + v.y) + (v.z + v.w);
     }
     const float mean_c = block_sum(sum, scratch) * inv_d;
     float sq = 0.f;
-    for (int j = tid; j < d; j += kCellThreads) {
-        const float v = row[j] - mean_c;
-        row[j] = v;
-        sq += v * v;
+    for (int j = tid * 4; j < d; j += kStride) {
+        float4 v = *reinterpret_cast<float4 *>(row + j);
+        v.x -= mean_c, v.y -= mean_c, v.z -= mean_c, v.w -= mean_c;
+        *reinterpret_cast<float4 *>(row + j) = v;
+        sq += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
     }
     const float rstd_c = 1.0f / sqrtf(block_sum(sq, scratch) * inv_d + eps);
     sum = 0.f;
-    for (int j = tid; j < d; j += kCellThreads) {
-        const float ae = alpha * widen16<kF16>(ep[j]);
-        float y = row[j] * rstd_c;
-        if (gamma_c) y *= gamma_c[j];
-        if (beta_c) y += beta_c[j];
-        const float zn = zp[j] * sigmoid_f(sp[j] + ae) + gelu_f(y) * sigmoid_f(sp[d + j] + ae);
-        z_out[(int64_t)r * d + j] = zn;
-        row[j] = zn;                                        // from here on: the new cell state
-        sum += zn;
+#pragma unroll 2
+    for (int j = tid * 4; j < d; j += kStride) {
+        const float4 e = widen16x4<kF16>(ep + j), sf = ld4(sp + j), si = ld4(sp + d + j), zo = ld4(zp + j);
+        const float4 ga = ld4_or(gamma_c, j, 1.f), be = ld4_or(beta_c, j, 0.f);
+        const float4 y = *reinterpret_cast<float4 *>(row + j);
+        float4 zn;
+        zn.x = zo.x * sigmoid_f(sf.x + alpha * e.x) + gelu_f(y.x * rstd_c * ga.x + be.x) * sigmoid_f(si.x + alpha * e.x);
+        zn.y = zo.y * sigmoid_f(sf.y + alpha * e.y) + gelu_f(y.y * rstd_c * ga.y + be.y) * sigmoid_f(si.y + alpha * e.y);
+        zn.z = zo.z * sigmoid_f(sf.z + alpha * e.z) + gelu_f(y.z * rstd_c * ga.z + be.z) * sigmoid_f(si.z + alpha * e.z);
+        zn.w = zo.w * sigmoid_f(sf.w + alpha * e.w) + gelu_f(y.w * rstd_c * ga.w + be.w) * sigmoid_f(si.w + alpha * e.w);
+        *reinterpret_cast<float4 *>(z_out + (int64_t)r * d + j) = zn;
+        *reinterpret_cast<float4 *>(row + j) = zn;          // from here on: the new cell state
+        sum += (zn.x + zn.y) + (zn.z + zn.w);
     }
     const float mean_z = block_sum(sum, scratch) * inv_d;
     sq = 0.f;
-    for (int j = tid; j < d; j += kCellThreads) {
-        const float v = row[j] - mean_z;
-        row[j] = v;
-        sq += v * v;
+    for (int j = tid * 4; j < d; j += kStride) {
+        float4 v = *reinterpret_cast<float4 *>(row + j);
+        v.x -= mean_z, v.y -= mean_z, v.z -= mean_z, v.w -= mean_z;
+        *reinterpret_cast<float4 *>(row + j) = v;
+        sq += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
     }
     const float rstd_z = 1.0f / sqrtf(block_sum(sq, scratch) * inv_d + eps);
-    for (int j = tid; j < d; j += kCellThreads) {
-        const float ae = alpha * widen16<kF16>(ep[j]);
-        float y = row[j] * rstd_z;
-        if (gamma_z) y *= gamma_z[j];
-        if (beta_z) y += beta_z[j];
-        const float hn = gelu_f(y) * sigmoid_f(sp[2 * d + j] + ae);
-        if (h_out) h_out[(int64_t)r * d + j] = narrow16<kF16>(hn);
-        if (h_out_f32) h_out_f32[(int64_t)r * d + j] = hn;
+#pragma unroll 2
+    for (int j = tid * 4; j < d; j += kStride) {
+        const float4 e = widen16x4<kF16>(ep + j), so = ld4(sp + 2 * d + j);
+        const float4 ga = ld4_or(gamma_z, j, 1.f), be = ld4_or(beta_z, j, 0.f);
+        const float4 y = *reinterpret_cast<float4 *>(row + j);
+        float4 hn;
+        hn.x = gelu_f(y.x * rstd_z * ga.x + be.x) * sigmoid_f(so.x + alpha * e.x);
+        hn.y = gelu_f(y.y * rstd_z * ga.y + be.y) * sigmoid_f(so.y + alpha * e.y);
+        hn.z = gelu_f(y.z * rstd_z * ga.z + be.z) * sigmoid_f(so.z + alpha * e.z);
+        hn.w = gelu_f(y.w * rstd_z * ga.w + be.w) * sigmoid_f(so.w + alpha * e.w);
+        if (h_out) {
+            uint2 pk;
+            pk.x = (uint32_t)narrow16<kF16>(hn.x) | ((uint32_t)narrow16<kF16>(hn.y) << 16);
+            pk.y = (uint32_t)narrow16<kF16>(hn.z) | ((uint32_t)narrow16<kF16>(hn.w) << 16);
+            *reinterpret_cast<uint2 *>(h_out + (int64_t)r * d + j) = pk;
+        }
+        if (h_out_f32) *reinterpret_cast<float4 *>(h_out_f32 + (int64_t)r * d + j) = hn;
     }
 }
 

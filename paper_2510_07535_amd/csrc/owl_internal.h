@@ -57,8 +57,10 @@ hipError_t launch_accept(const int32_t *tokens, const int32_t *parent, const int
 hipError_t launch_commit(const owl_verify_desc &d, void *k_cache, void *v_cache, const int32_t *page_table,
                          const int32_t *ctx_lens, const int32_t *accepted, const int32_t *n_accept,
                          int32_t *new_ctx_lens, uint32_t *status, hipStream_t s);
-hipError_t launch_drafter_proj(int dtype, const void *h, const void *w, float *s, int P, int d_in, int d,
-                               hipStream_t st);
+hipError_t launch_drafter_proj(int dtype, const void *h, const void *w, bool tiled, float *s, int P, int d_in,
+                               int d, hipStream_t st);
+size_t drafter_tiled_bytes(int d_in, int d);
+hipError_t launch_drafter_tile_weights(const void *w_rows, void *w_tiled, int d_in, int d, hipStream_t st);
 hipError_t launch_drafter_gates(int dtype, const float *s, const float *z, const int32_t *tokens,
                                 const int32_t *parent_row, const void *emb, const float *gamma_c,
                                 const float *beta_c, const float *gamma_z, const float *beta_z, void *h_out,

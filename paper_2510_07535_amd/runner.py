@@ -69,7 +69,7 @@ class VerifyStep:
 class DrafterStep:
     """Device residency for one step of the drafter's cell on a ``workloads.DrafterCase``."""
 
-    def __init__(self, case: W.DrafterCase, alpha: float, device: str = "cuda:0"):
+    def __init__(self, case: W.DrafterCase, alpha: float, device: str = "cuda:0", tiled: bool = True):
         self.case = case
         self.device = torch.device(device)
         up = lambda a: None if a is None else _to_dev(np.ascontiguousarray(a), self.device)
@@ -82,7 +82,12 @@ class DrafterStep:
         self.z_out = torch.zeros((case.M, case.d), dtype=torch.float32, device=self.device)
         self.status = torch.zeros(1, dtype=torch.int32, device=self.device)
         self.desc = B.DrafterDesc(d_in=case.d_in, d=case.d, n_states=case.P, n_rows=case.M, vocab=case.vocab,
-                                  dtype=case.dtype, alpha=alpha, eps=case.eps)
+                                  dtype=case.dtype, alpha=alpha, eps=case.eps,
+                                  w_layout=B.OWL_W_TILED if tiled else B.OWL_W_ROWS)
+        if tiled:                                            # the library's own one-time re-layout of the weights
+            self.w_rows = self.w
+            self.w = torch.empty(B.owl_drafter_tiled_weight_bytes(self.desc), dtype=torch.uint8, device=self.device)
+            B.owl_drafter_tile_weights(self.desc, self.w_rows, self.w)
         self.workspace = torch.empty(B.owl_drafter_cell_workspace_size(self.desc), dtype=torch.uint8,
                                      device=self.device)
 

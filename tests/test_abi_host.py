@@ -181,7 +181,11 @@ def _drafter(**over):
 
 
 def test_drafter_struct_and_workspace():
-    assert ctypes.sizeof(B.DrafterDesc) == 8 * 4
+    assert ctypes.sizeof(B.DrafterDesc) == 10 * 4
+    # 4 * 12288 rows in groups of 64, 12288 / 32 k-steps, 4 KiB per (group, k-step)
+    assert B.owl_drafter_tiled_weight_bytes(_drafter()) == (4 * 12288 // 64) * (12288 // 32) * 4096 == 4 * 12288 * 12288 * 2
+    assert B.owl_drafter_tiled_weight_bytes(_drafter(d=48, d_in=96)) == 3 * 3 * 4096
+    assert B.owl_drafter_tiled_weight_bytes(_drafter(d=16, d_in=32)) == 4096     # one padded group
     assert B.owl_drafter_cell_workspace_size(_drafter()) == 10 * 4 * 12288 * 4
 
 
@@ -196,6 +200,7 @@ def test_drafter_struct_and_workspace():
     (dict(eps=-1.0), B.OWL_ERR_INVALID_ARG),
     (dict(alpha=float("nan")), B.OWL_ERR_INVALID_ARG),
     (dict(vocab=0), B.OWL_ERR_INVALID_ARG),
+    (dict(w_layout=2), B.OWL_ERR_UNSUPPORTED),
 ])
 def test_drafter_bad_descriptors_are_rejected(over, code):
     with pytest.raises(B.OwlError) as e:
@@ -216,6 +221,9 @@ def test_drafter_cell_rejects_before_launch():
     assert call(d, w=None) == B.OWL_ERR_INVALID_ARG
     assert call(d, z_out=None) == B.OWL_ERR_INVALID_ARG
     assert call(d, w=fake + 2) == B.OWL_ERR_INVALID_ARG
+    assert call(d, z=fake + 4) == B.OWL_ERR_INVALID_ARG
+    assert lib.owl_drafter_tile_weights(ctypes.byref(d), None, fake, None) == B.OWL_ERR_INVALID_ARG
+    assert lib.owl_drafter_tile_weights(ctypes.byref(d), fake, fake + 8, None) == B.OWL_ERR_INVALID_ARG
     assert call(d, phases=0) == B.OWL_ERR_INVALID_ARG
     assert call(d, phases=4) == B.OWL_ERR_INVALID_ARG
     assert call(d, ws=None) == B.OWL_ERR_WORKSPACE

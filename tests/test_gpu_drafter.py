@@ -22,8 +22,8 @@ pytestmark = pytest.mark.gpu
 TOL = 2e-4
 
 
-def _check(case, alpha, rows=None):
-    step = DrafterStep(case, alpha)
+def _check(case, alpha, rows=None, tiled=True):
+    step = DrafterStep(case, alpha, tiled=tiled)
     step.run()
     h32, h16, z1 = step.result()
     assert step.dev_status() == 0
@@ -52,7 +52,30 @@ def _check(case, alpha, rows=None):
 def test_cell_matches_oracle(dtype, d_in, d, P, M):
     case = W.make_drafter_case("t", 100 + d, dtype=dtype, d_in=d_in, d=d, P=P, M=M, vocab=50)
     _check(case, 1.0)                                    # alpha = 1: the embedding weighs as much as the projection
-    _check(case, OD.drafter_alpha(8, d))                 # the paper's alpha
+    _check(case, OD.drafter_alpha(8, d), tiled=False)    # the paper's alpha; weights as a plain [4d][d_in] matrix
+
+
+def _tiled_by_definition(w_bits, d_in, d):
+    """The tiled layout built from its definition in the header, granule by granule."""
+    rows = w_bits.reshape(4 * d, d_in)
+    groups = -(-4 * d // 64)
+    out = np.zeros((groups * (d_in // 32) * 4 * 64, 8), dtype=np.uint16)
+    for row in range(4 * d):
+        for k in range(0, d_in, 8):
+            g = ((row // 64 * (d_in // 32) + k // 32) * 4 + row % 64 // 16) * 64 + (k % 32 // 8) * 16 + row % 16
+            out[g] = rows[row, k:k + 8]
+    return out.reshape(-1)
+
+
+@pytest.mark.parametrize("d_in,d", [(32, 16), (96, 48), (160, 272)])
+def test_tiled_weights_are_the_documented_permutation(d_in, d):
+    case = W.make_drafter_case("t", 5, d_in=d_in, d=d, P=1, M=1)
+    step = DrafterStep(case, 1.0, tiled=True)
+    torch.cuda.synchronize()
+    got = step.w.cpu().numpy().view(np.uint16)
+    want = _tiled_by_definition(case.W, d_in, d)
+    assert got.size == want.size == B.owl_drafter_tiled_weight_bytes(step.desc) // 2
+    assert np.array_equal(got, want)
 
 
 def test_identity_rows_and_zero_start():
@@ -137,3 +160,4 @@ def test_full_width_sampled_rows():
     (Appendix A.1: top-k 10) continuing ten states: three rows checked against the oracle."""
     case = W.make_drafter_case("level", 21, d_in=12288, d=12288, P=10, M=10, vocab=512)
     _check(case, OD.drafter_alpha(8, 12288), rows=np.array([0, 4, 9]))
+    _check(case, OD.drafter_alpha(8, 12288), rows=np.array([7]), tiled=False)
