@@ -364,7 +364,8 @@ owl_status owl_drafter_cell_workspace_size(const owl_drafter_desc *desc, size_t 
     owl_status st = check_drafter(desc);
     if (st != OWL_OK) return st;
     if (!bytes) return OWL_ERR_INVALID_ARG;
-    *bytes = (size_t)desc->n_states * 4 * desc->d * sizeof(float);
+    // the projections [P][4d], then the chunk statistics of the two normalisations
+    *bytes = ((size_t)desc->n_states * 4 * desc->d + drafter_gate_scratch_floats(desc->n_rows)) * sizeof(float);
     return OWL_OK;
 }
 
@@ -395,7 +396,8 @@ owl_status owl_drafter_cell_phases(const owl_drafter_desc *desc, const void *h, 
             return OWL_ERR_HIP;
     if (phases & OWL_DRAFTER_GATES)
         if (launch_drafter_gates(desc->dtype, proj, z, tokens, parent_row, emb, gamma_c, beta_c, gamma_z, beta_z,
-                                 h_out, h_out_f32, z_out, desc->n_states, desc->n_rows, desc->d, desc->vocab,
+                                 h_out, h_out_f32, z_out, proj + (size_t)desc->n_states * 4 * desc->d, desc->n_states,
+                                 desc->n_rows, desc->d, desc->vocab,
                                  desc->alpha, desc->eps, dev_status, s) != hipSuccess)
             return OWL_ERR_HIP;
     return OWL_OK;

@@ -4,15 +4,14 @@
 //     z'  = z g^f + c                              h'  = f(z') g^o
 // with f = layer normalisation over the d channels followed by GeLU.
 //
-// Two kernels.  The projection W^m h reads every weight exactly once (4 d d_in
+// The projection W^m h reads every weight exactly once (4 d d_in
 // elements, 1.2 GB for the paper's d = 12288 with a square W) against at most
 // 64 state rows: a streaming read of HBM with a thin contraction on the side,
 // done with MFMA only because 64 rows x 4 d x d_in multiply-adds per step are
 // beyond the vector ALUs at that rate.  Weights go from global memory straight
 // into the MFMA operand registers: no element is used twice, so there is
-// nothing to stage in LDS.  The gate kernel then needs whole-row statistics
-// twice (of s^c and of z'), which is why it is a launch of its own: one
-// workgroup per row keeps the row on chip and reduces across the workgroup.
+// nothing to stage in LDS.  The gates then need whole-row statistics twice (of
+// s^c and of z'): three small launches, see below.
 #include "owl_device.h"
 
 namespace owl {
@@ -213,14 +212,21 @@ hipError_t launch_drafter_tile_weights(const void *w_rows, void *w_tiled, int d_
 }
 
 // ---------------------------------------------------------------------------
-// Gates and state update: one workgroup of 1024 threads per row of the step,
-// thread t owning the channels t, t + 1024, ...  The mean and the centred sum of
-// squares of the two normalisations are each a reduction over the workgroup;
-// between them the row being normalised (first s^c, then z') waits in LDS, every
-// thread reading back only what it wrote itself.  The gates are formed where they
-// are used, from projections that sit in L2.
+// Gates and state update.  f needs the mean and variance of a whole row twice
+// (of s^c, then of z'), and the transcendental work of one row (three sigmoids
+// and two GeLUs per channel) keeps a single compute unit busy for ~20 us, so a
+// row is spread over workgroups of 256 threads x 4 channels and the two row
+// statistics travel through memory between three small launches:
+//   1. per chunk of 1024 channels: count, mean and centred sum of squares of s^c
+//   2. merge those; z' = z g^f + f(s^c) g^i; the same partials of z'
+//   3. merge those; h' = f(z') g^o
+// Partials are (mean, M2) pairs merged with the pairwise update
+//     M2 = sum_c M2_c + n_c (mean_c - mean)^2 ,
+// which keeps the variance as accurate as a two-pass sum.
 // ---------------------------------------------------------------------------
-constexpr int kCellThreads = 1024;
+constexpr int kGateThreads = 256;
+constexpr int kGateChunk = kGateThreads * 4;               // channels per workgroup
+constexpr int kGateMaxChunks = 16;                         // d <= 16384
 
 __device__ __forceinline__ float block_sum(float v, float *scratch)
 {
@@ -232,7 +238,7 @@ __device__ __forceinline__ float block_sum(float v, float *scratch)
     __syncthreads();
     float t = 0.f;
 #pragma unroll
-    for (int i = 0; i < kCellThreads / 64; ++i) t += scratch[i];   // same order in every thread
+    for (int i = 0; i < kGateThreads / 64; ++i) t += scratch[i];   // same order in every thread
     return t;
 }
 
@@ -257,12 +263,12 @@ template <bool kF16> __device__ __forceinline__ uint16_t narrow16(float x)
     }
 }
 
-// Four consecutive channels of a 16-bit row as floats.
-template <bool kF16> __device__ __forceinline__ float4 widen16x4(const uint16_t *p)
+// alpha * (four consecutive channels of a 16-bit embedding row)
+template <bool kF16> __device__ __forceinline__ float4 scaled_emb4(const uint16_t *p, float alpha)
 {
     const uint2 raw = *reinterpret_cast<const uint2 *>(p);
-    return make_float4(widen16<kF16>((uint16_t)(raw.x & 0xffffu)), widen16<kF16>((uint16_t)(raw.x >> 16)),
-                       widen16<kF16>((uint16_t)(raw.y & 0xffffu)), widen16<kF16>((uint16_t)(raw.y >> 16)));
+    return make_float4(alpha * widen16<kF16>((uint16_t)(raw.x & 0xffffu)), alpha * widen16<kF16>((uint16_t)(raw.x >> 16)),
+                       alpha * widen16<kF16>((uint16_t)(raw.y & 0xffffu)), alpha * widen16<kF16>((uint16_t)(raw.y >> 16)));
 }
 
 __device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
@@ -270,128 +276,159 @@ __device__ __forceinline__ float4 ld4_or(const float *p, int j, float fill)
 {
     return p ? ld4(p + j) : make_float4(fill, fill, fill, fill);
 }
+__device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
 
-// Every thread owns groups of four consecutive channels (d is a multiple of 16),
-// so that each pass is a handful of independent 16-byte loads per thread rather
-// than a chain of dependent ones.
-template <bool kF16>
-__global__ void __launch_bounds__(kCellThreads) drafter_gates_kernel(
-    const float *__restrict__ s, const float *__restrict__ z, const int32_t *__restrict__ tokens,
-    const int32_t *__restrict__ parent_row, const uint16_t *__restrict__ emb, const float *__restrict__ gamma_c,
-    const float *__restrict__ beta_c, const float *__restrict__ gamma_z, const float *__restrict__ beta_z,
-    uint16_t *__restrict__ h_out, float *__restrict__ h_out_f32, float *__restrict__ z_out, int P, int d,
-    int vocab, float alpha, float eps, uint32_t *status)
+struct GateArgs {
+    const float *s, *z;
+    const int32_t *tokens, *parent_row;
+    const uint16_t *emb;
+    const float *gamma_c, *beta_c, *gamma_z, *beta_z;
+    uint16_t *h_out;
+    float *h_out_f32, *z_out;
+    float *part_c, *part_z;       // [M][kGateMaxChunks][2]: mean and centred sum of squares per chunk
+    int P, d, vocab;
+    float alpha, eps;
+    uint32_t *status;
+};
+
+// What every gate kernel needs first: the row's state, its token's embedding
+// row and the embedding weight (0 for a token outside the table).
+struct GateRow {
+    const float *sp, *zp;
+    const uint16_t *ep;
+    float alpha;
+};
+
+__device__ __forceinline__ GateRow gate_row(const GateArgs &a, int r, bool flag)
 {
-    extern __shared__ float lds[];
-    float *scratch = lds;                                   // kCellThreads / 64 partial sums
-    float *row = lds + kCellThreads / 64;                   // d floats
-    const int r = blockIdx.x, tid = threadIdx.x;
-    int p = parent_row ? parent_row[r] : r;
-    if (p < 0 || p >= P) {
-        if (tid == 0) flag_status(status, OWL_DEV_BAD_ROW);
+    int p = a.parent_row ? a.parent_row[r] : r;
+    if (p < 0 || p >= a.P) {
+        if (flag && threadIdx.x == 0) flag_status(a.status, OWL_DEV_BAD_ROW);
         p = 0;
     }
-    int tok = tokens[r];
-    if (tok < 0 || tok >= vocab) {
-        if (tid == 0) flag_status(status, OWL_DEV_BAD_TOKEN);
+    int tok = a.tokens[r];
+    float alpha = a.alpha;
+    if (tok < 0 || tok >= a.vocab) {
+        if (flag && threadIdx.x == 0) flag_status(a.status, OWL_DEV_BAD_TOKEN);
         tok = 0;
-        alpha = 0.f;                                        // e = 0 for this row
+        alpha = 0.f;
     }
-    const float *sp = s + (int64_t)p * 4 * d;
-    const float *zp = z + (int64_t)p * d;
-    const uint16_t *ep = emb + (int64_t)tok * d;
-    const float inv_d = 1.0f / (float)d;
-    constexpr int kStride = kCellThreads * 4;
+    return GateRow{a.s + (int64_t)p * 4 * a.d, a.z + (int64_t)p * a.d, a.emb + (int64_t)tok * a.d, alpha};
+}
 
-    float sum = 0.f;
-#pragma unroll 4
-    for (int j = tid * 4; j < d; j += kStride) {
-        const float4 e = widen16x4<kF16>(ep + j), c = ld4(sp + 3 * d + j);
-        const float4 v = make_float4(c.x + alpha * e.x, c.y + alpha * e.y, c.z + alpha * e.z, c.w + alpha * e.w);
-        *reinterpret_cast<float4 *>(row + j) = v;
-        sum += (v.x + v.y) + (v.z + v.w);
-    }
-    const float mean_c = block_sum(sum, scratch) * inv_d;
+// Mean and centred sum of squares of the live channels of this workgroup's chunk.
+__device__ __forceinline__ void chunk_stats(float4 v, bool live, int n_live, float *scratch, float *out2)
+{
+    const float sum = block_sum(live ? (v.x + v.y) + (v.z + v.w) : 0.f, scratch);
+    const float mean = sum / (float)n_live;
     float sq = 0.f;
-    for (int j = tid * 4; j < d; j += kStride) {
-        float4 v = *reinterpret_cast<float4 *>(row + j);
-        v.x -= mean_c, v.y -= mean_c, v.z -= mean_c, v.w -= mean_c;
-        *reinterpret_cast<float4 *>(row + j) = v;
-        sq += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+    if (live) {
+        v.x -= mean, v.y -= mean, v.z -= mean, v.w -= mean;
+        sq = (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
     }
-    const float rstd_c = 1.0f / sqrtf(block_sum(sq, scratch) * inv_d + eps);
-    sum = 0.f;
-#pragma unroll 2
-    for (int j = tid * 4; j < d; j += kStride) {
-        const float4 e = widen16x4<kF16>(ep + j), sf = ld4(sp + j), si = ld4(sp + d + j), zo = ld4(zp + j);
-        const float4 ga = ld4_or(gamma_c, j, 1.f), be = ld4_or(beta_c, j, 0.f);
-        const float4 y = *reinterpret_cast<float4 *>(row + j);
-        float4 zn;
-        zn.x = zo.x * sigmoid_f(sf.x + alpha * e.x) + gelu_f(y.x * rstd_c * ga.x + be.x) * sigmoid_f(si.x + alpha * e.x);
-        zn.y = zo.y * sigmoid_f(sf.y + alpha * e.y) + gelu_f(y.y * rstd_c * ga.y + be.y) * sigmoid_f(si.y + alpha * e.y);
-        zn.z = zo.z * sigmoid_f(sf.z + alpha * e.z) + gelu_f(y.z * rstd_c * ga.z + be.z) * sigmoid_f(si.z + alpha * e.z);
-        zn.w = zo.w * sigmoid_f(sf.w + alpha * e.w) + gelu_f(y.w * rstd_c * ga.w + be.w) * sigmoid_f(si.w + alpha * e.w);
-        *reinterpret_cast<float4 *>(z_out + (int64_t)r * d + j) = zn;
-        *reinterpret_cast<float4 *>(row + j) = zn;          // from here on: the new cell state
-        sum += (zn.x + zn.y) + (zn.z + zn.w);
+    const float m2 = block_sum(sq, scratch);
+    if (threadIdx.x == 0) out2[0] = mean, out2[1] = m2;
+}
+
+// Mean and 1 / sqrt(variance + eps) of a row from its chunks' partials.
+__device__ __forceinline__ void merge_stats(const float *part, int d, float eps, float *mean_out, float *rstd_out)
+{
+    const int n_chunks = (d + kGateChunk - 1) / kGateChunk;
+    float mean = 0.f;
+    for (int c = 0; c < n_chunks; ++c) mean += part[2 * c] * (float)min(kGateChunk, d - c * kGateChunk);
+    mean /= (float)d;
+    float m2 = 0.f;
+    for (int c = 0; c < n_chunks; ++c) {
+        const float dm = part[2 * c] - mean;
+        m2 += part[2 * c + 1] + (float)min(kGateChunk, d - c * kGateChunk) * dm * dm;
     }
-    const float mean_z = block_sum(sum, scratch) * inv_d;
-    sq = 0.f;
-    for (int j = tid * 4; j < d; j += kStride) {
-        float4 v = *reinterpret_cast<float4 *>(row + j);
-        v.x -= mean_z, v.y -= mean_z, v.z -= mean_z, v.w -= mean_z;
-        *reinterpret_cast<float4 *>(row + j) = v;
-        sq += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
-    }
-    const float rstd_z = 1.0f / sqrtf(block_sum(sq, scratch) * inv_d + eps);
-#pragma unroll 2
-    for (int j = tid * 4; j < d; j += kStride) {
-        const float4 e = widen16x4<kF16>(ep + j), so = ld4(sp + 2 * d + j);
-        const float4 ga = ld4_or(gamma_z, j, 1.f), be = ld4_or(beta_z, j, 0.f);
-        const float4 y = *reinterpret_cast<float4 *>(row + j);
-        float4 hn;
-        hn.x = gelu_f(y.x * rstd_z * ga.x + be.x) * sigmoid_f(so.x + alpha * e.x);
-        hn.y = gelu_f(y.y * rstd_z * ga.y + be.y) * sigmoid_f(so.y + alpha * e.y);
-        hn.z = gelu_f(y.z * rstd_z * ga.z + be.z) * sigmoid_f(so.z + alpha * e.z);
-        hn.w = gelu_f(y.w * rstd_z * ga.w + be.w) * sigmoid_f(so.w + alpha * e.w);
-        if (h_out) {
-            uint2 pk;
-            pk.x = (uint32_t)narrow16<kF16>(hn.x) | ((uint32_t)narrow16<kF16>(hn.y) << 16);
-            pk.y = (uint32_t)narrow16<kF16>(hn.z) | ((uint32_t)narrow16<kF16>(hn.w) << 16);
-            *reinterpret_cast<uint2 *>(h_out + (int64_t)r * d + j) = pk;
-        }
-        if (h_out_f32) *reinterpret_cast<float4 *>(h_out_f32 + (int64_t)r * d + j) = hn;
-    }
+    *mean_out = mean;
+    *rstd_out = 1.0f / sqrtf(m2 / (float)d + eps);
 }
 
 template <bool kF16>
-static hipError_t launch_gates_dt(const float *s, const float *z, const int32_t *tokens, const int32_t *parent_row,
-                                  const void *emb, const float *gamma_c, const float *beta_c, const float *gamma_z,
-                                  const float *beta_z, void *h_out, float *h_out_f32, float *z_out, int P, int M,
-                                  int d, int vocab, float alpha, float eps, uint32_t *status, hipStream_t st)
+__global__ void __launch_bounds__(kGateThreads) drafter_stats_kernel(GateArgs a)
 {
-    const size_t lds = ((size_t)d + kCellThreads / 64) * sizeof(float);
-    if (lds > 64 * 1024) {                                  // beyond the default cap of dynamic LDS
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&drafter_gates_kernel<kF16>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
+    __shared__ float scratch[kGateThreads / 64];
+    const int c = blockIdx.x, r = blockIdx.y, j = c * kGateChunk + threadIdx.x * 4;
+    const GateRow g = gate_row(a, r, c == 0);
+    const bool live = j < a.d;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (live) v = add4(ld4(g.sp + 3 * a.d + j), scaled_emb4<kF16>(g.ep + j, g.alpha));
+    chunk_stats(v, live, min(kGateChunk, a.d - c * kGateChunk), scratch, a.part_c + ((int64_t)r * kGateMaxChunks + c) * 2);
+}
+
+template <bool kF16>
+__global__ void __launch_bounds__(kGateThreads) drafter_state_kernel(GateArgs a)
+{
+    __shared__ float scratch[kGateThreads / 64];
+    const int c = blockIdx.x, r = blockIdx.y, j = c * kGateChunk + threadIdx.x * 4;
+    const GateRow g = gate_row(a, r, false);
+    float mean, rstd;
+    merge_stats(a.part_c + (int64_t)r * kGateMaxChunks * 2, a.d, a.eps, &mean, &rstd);
+    const bool live = j < a.d;
+    float4 zn = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (live) {
+        const float4 e = scaled_emb4<kF16>(g.ep + j, g.alpha);
+        const float4 sf = add4(ld4(g.sp + j), e), si = add4(ld4(g.sp + a.d + j), e), sc = add4(ld4(g.sp + 3 * a.d + j), e);
+        const float4 zo = ld4(g.zp + j), ga = ld4_or(a.gamma_c, j, 1.f), be = ld4_or(a.beta_c, j, 0.f);
+        zn.x = zo.x * sigmoid_f(sf.x) + gelu_f((sc.x - mean) * rstd * ga.x + be.x) * sigmoid_f(si.x);
+        zn.y = zo.y * sigmoid_f(sf.y) + gelu_f((sc.y - mean) * rstd * ga.y + be.y) * sigmoid_f(si.y);
+        zn.z = zo.z * sigmoid_f(sf.z) + gelu_f((sc.z - mean) * rstd * ga.z + be.z) * sigmoid_f(si.z);
+        zn.w = zo.w * sigmoid_f(sf.w) + gelu_f((sc.w - mean) * rstd * ga.w + be.w) * sigmoid_f(si.w);
+        *reinterpret_cast<float4 *>(a.z_out + (int64_t)r * a.d + j) = zn;
     }
-    hipLaunchKernelGGL(drafter_gates_kernel<kF16>, dim3(M), dim3(kCellThreads), lds, st, s, z, tokens, parent_row,
-                       static_cast<const uint16_t *>(emb), gamma_c, beta_c, gamma_z, beta_z,
-                       static_cast<uint16_t *>(h_out), h_out_f32, z_out, P, d, vocab, alpha, eps, status);
+    chunk_stats(zn, live, min(kGateChunk, a.d - c * kGateChunk), scratch, a.part_z + ((int64_t)r * kGateMaxChunks + c) * 2);
+}
+
+template <bool kF16>
+__global__ void __launch_bounds__(kGateThreads) drafter_hidden_kernel(GateArgs a)
+{
+    const int c = blockIdx.x, r = blockIdx.y, j = c * kGateChunk + threadIdx.x * 4;
+    const GateRow g = gate_row(a, r, false);
+    float mean, rstd;
+    merge_stats(a.part_z + (int64_t)r * kGateMaxChunks * 2, a.d, a.eps, &mean, &rstd);
+    if (j >= a.d) return;
+    const float4 so = add4(ld4(g.sp + 2 * a.d + j), scaled_emb4<kF16>(g.ep + j, g.alpha));
+    const float4 zn = ld4(a.z_out + (int64_t)r * a.d + j), ga = ld4_or(a.gamma_z, j, 1.f), be = ld4_or(a.beta_z, j, 0.f);
+    float4 hn;
+    hn.x = gelu_f((zn.x - mean) * rstd * ga.x + be.x) * sigmoid_f(so.x);
+    hn.y = gelu_f((zn.y - mean) * rstd * ga.y + be.y) * sigmoid_f(so.y);
+    hn.z = gelu_f((zn.z - mean) * rstd * ga.z + be.z) * sigmoid_f(so.z);
+    hn.w = gelu_f((zn.w - mean) * rstd * ga.w + be.w) * sigmoid_f(so.w);
+    if (a.h_out) {
+        uint2 pk;
+        pk.x = (uint32_t)narrow16<kF16>(hn.x) | ((uint32_t)narrow16<kF16>(hn.y) << 16);
+        pk.y = (uint32_t)narrow16<kF16>(hn.z) | ((uint32_t)narrow16<kF16>(hn.w) << 16);
+        *reinterpret_cast<uint2 *>(a.h_out + (int64_t)r * a.d + j) = pk;
+    }
+    if (a.h_out_f32) *reinterpret_cast<float4 *>(a.h_out_f32 + (int64_t)r * a.d + j) = hn;
+}
+
+size_t drafter_gate_scratch_floats(int M) { return (size_t)2 * M * kGateMaxChunks * 2; }
+
+template <bool kF16> static hipError_t launch_gates_dt(const GateArgs &a, int M, hipStream_t st)
+{
+    const dim3 grid((a.d + kGateChunk - 1) / kGateChunk, M), block(kGateThreads);
+    hipLaunchKernelGGL(drafter_stats_kernel<kF16>, grid, block, 0, st, a);
+    hipLaunchKernelGGL(drafter_state_kernel<kF16>, grid, block, 0, st, a);
+    hipLaunchKernelGGL(drafter_hidden_kernel<kF16>, grid, block, 0, st, a);
     return hipGetLastError();
 }
 
 hipError_t launch_drafter_gates(int dtype, const float *s, const float *z, const int32_t *tokens,
                                 const int32_t *parent_row, const void *emb, const float *gamma_c,
                                 const float *beta_c, const float *gamma_z, const float *beta_z, void *h_out,
-                                float *h_out_f32, float *z_out, int P, int M, int d, int vocab, float alpha,
-                                float eps, uint32_t *status, hipStream_t st)
+                                float *h_out_f32, float *z_out, float *gate_scratch, int P, int M, int d, int vocab,
+                                float alpha, float eps, uint32_t *status, hipStream_t st)
 {
-    return dtype == OWL_F16 ? launch_gates_dt<true>(s, z, tokens, parent_row, emb, gamma_c, beta_c, gamma_z, beta_z,
-                                                    h_out, h_out_f32, z_out, P, M, d, vocab, alpha, eps, status, st)
-                            : launch_gates_dt<false>(s, z, tokens, parent_row, emb, gamma_c, beta_c, gamma_z, beta_z,
-                                                     h_out, h_out_f32, z_out, P, M, d, vocab, alpha, eps, status, st);
+    GateArgs a;
+    a.s = s, a.z = z, a.tokens = tokens, a.parent_row = parent_row, a.emb = static_cast<const uint16_t *>(emb);
+    a.gamma_c = gamma_c, a.beta_c = beta_c, a.gamma_z = gamma_z, a.beta_z = beta_z;
+    a.h_out = static_cast<uint16_t *>(h_out), a.h_out_f32 = h_out_f32, a.z_out = z_out;
+    a.part_c = gate_scratch, a.part_z = gate_scratch + (size_t)M * kGateMaxChunks * 2;
+    a.P = P, a.d = d, a.vocab = vocab, a.alpha = alpha, a.eps = eps, a.status = status;
+    return dtype == OWL_F16 ? launch_gates_dt<true>(a, M, st) : launch_gates_dt<false>(a, M, st);
 }
 
 }  // namespace owl

@@ -64,8 +64,9 @@ hipError_t launch_drafter_tile_weights(const void *w_rows, void *w_tiled, int d_
 hipError_t launch_drafter_gates(int dtype, const float *s, const float *z, const int32_t *tokens,
                                 const int32_t *parent_row, const void *emb, const float *gamma_c,
                                 const float *beta_c, const float *gamma_z, const float *beta_z, void *h_out,
-                                float *h_out_f32, float *z_out, int P, int M, int d, int vocab, float alpha,
-                                float eps, uint32_t *status, hipStream_t st);
+                                float *h_out_f32, float *z_out, float *gate_scratch, int P, int M, int d, int vocab,
+                                float alpha, float eps, uint32_t *status, hipStream_t st);
+size_t drafter_gate_scratch_floats(int M);
 hipError_t launch_tree_mask(const int32_t *parent, int B, int N, uint64_t *anc, int32_t *depth,
                             uint32_t *status, hipStream_t s);
 hipError_t launch_gather(const owl_verify_desc &d, const void *cache, const int32_t *page_table,

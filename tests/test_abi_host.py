@@ -186,7 +186,7 @@ def test_drafter_struct_and_workspace():
     assert B.owl_drafter_tiled_weight_bytes(_drafter()) == (4 * 12288 // 64) * (12288 // 32) * 4096 == 4 * 12288 * 12288 * 2
     assert B.owl_drafter_tiled_weight_bytes(_drafter(d=48, d_in=96)) == 3 * 3 * 4096
     assert B.owl_drafter_tiled_weight_bytes(_drafter(d=16, d_in=32)) == 4096     # one padded group
-    assert B.owl_drafter_cell_workspace_size(_drafter()) == 10 * 4 * 12288 * 4
+    assert B.owl_drafter_cell_workspace_size(_drafter()) == (10 * 4 * 12288 + 2 * 10 * 16 * 2) * 4
 
 
 @pytest.mark.parametrize("over,code", [

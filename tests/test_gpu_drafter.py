@@ -125,7 +125,7 @@ def test_phases_split():
     for a, b in zip(want, got):
         assert np.array_equal(a, b)
     # the projection in the workspace is W^m h: sampled entries against the plain definition
-    proj = parts.workspace.cpu().numpy().view(np.float32).reshape(case.P, 4, case.d)
+    proj = parts.workspace.cpu().numpy().view(np.float32)[:case.P * 4 * case.d].reshape(case.P, 4, case.d)
     Wm, h = W.widen(case.W, case.dtype), W.widen(case.h, case.dtype)
     r = np.random.Generator(np.random.Philox(key=1))
     for _ in range(50):
