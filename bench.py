@@ -33,12 +33,12 @@ MIN_ROTATION_BYTES = 2 << 30
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
 
 
-def measured_traffic(workload):
-    """HBM bytes per split-KV launch from the committed rocprofv3 counter runs
+def measured_traffic(workload, kernel="splitkv_kernel"):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter runs
     (FETCH_SIZE + WRITE_SIZE, calibrated), or None if none was recorded."""
     try:
         with open(TRAFFIC_FILE) as f:
-            return json.load(f)["splitkv_kernel"][workload]["hbm_bytes_per_launch"]
+            return json.load(f)[kernel][workload]["hbm_bytes_per_launch"]
     except (OSError, KeyError, ValueError):
         return None
 
@@ -285,7 +285,8 @@ def bench_drafter(steps=60, with_cpu=True):
                "weight_bytes": wbytes, "weight_layout": "tiled", "weight_copies_rotated": len(copies), "us_per_step": sec * 1e6,
                "GBps": wbytes / sec / 1e9,
                "roofline": {"bound": "hbm", "achieved": wbytes / ksec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                            "frac": wbytes / ksec / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                            "frac": wbytes / ksec / 1e9 / HBM_PEAK_GBS,
+                            "traffic": measured_traffic(name, "drafter_proj_kernel"),
                             "kernel": "drafter_proj_kernel", "kernel_avg_us": ksec * 1e6,
                             "algorithmic_bytes_per_launch": wbytes}}
         if with_cpu and name == DRAFTER_SHAPES[0][0]:
