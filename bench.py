@@ -145,14 +145,37 @@ def mfma_probe_tflops(kind="random", iters=20000):
         src = torch.ones(n, device="cuda", dtype=torch.bfloat16)
     nwg = 256
     sink = torch.zeros(nwg * 512, dtype=torch.float32, device="cuda")
+    ghz = torch.zeros(nwg, dtype=torch.float32, device="cuda")
     B.owl_mfma_probe(src, 2000, sink, nwg)
     torch.cuda.synchronize()
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a.record()
-    B.owl_mfma_probe(src, iters, sink, nwg)
+    B.owl_mfma_probe(src, iters, sink, nwg, clock_ghz=ghz)
     b.record()
     torch.cuda.synchronize()
-    return nwg * 8 * iters * 16 * 16384.0 / (a.elapsed_time(b) * 1e-3) / 1e12
+    return nwg * 8 * iters * 16 * 16384.0 / (a.elapsed_time(b) * 1e-3) / 1e12, float(ghz.median().item())
+
+
+def kernel_shader_clock(rot):
+    """Median shader clock (GHz) over the workgroups of one split-KV launch of the timed
+    workload: shader cycles per constant-rate tick across the main loop (the timeline hook)."""
+    import torch
+    from paper_2510_07535_amd import binding as B
+    nwg = rot.step.plan.n_workgroups
+    buf = torch.zeros(10 * nwg, dtype=torch.int64, device="cuda")
+    B.owl_debug_set_timeline(buf)
+    try:
+        for _ in range(60):                              # steady state: the clock governor averages over
+            rot.run()                                    # milliseconds; the last launch's record is read
+        torch.cuda.synchronize()
+    finally:
+        B.owl_debug_set_timeline(None)
+    t = buf.cpu().numpy().reshape(nwg, 10)
+    t = t[(t[:, 3] - t[:, 2]) >= 200]                    # main loops of at least 2 us: the tick is 10 ns
+    if len(t) == 0:
+        return None
+    import numpy as np
+    return float(np.median((t[:, 9] - t[:, 8]) / ((t[:, 3] - t[:, 2]) * 10.0)))
 
 
 def cpu_baseline(case, budget_rows=None):
@@ -363,8 +386,12 @@ def main():
                                 "algorithmic_flop_per_launch": flop}
     if not args.no_probe:
         line["roofline"]["stream_read_probe_GBps"] = stream_probe_gbs()
-        line["roofline"]["mfma"]["probe_random_operands_TFLOPs"] = mfma_probe_tflops("random")
-        line["roofline"]["mfma"]["probe_constant_operands_TFLOPs"] = mfma_probe_tflops("ones")
+        # the chip is power-limited: the shader clock under load, read inside the kernels, next to the rates
+        line["roofline"]["shader_clock_GHz"] = {"nominal": 2.4, "splitkv_kernel": kernel_shader_clock(rot)}
+        for kind, key in (("random", "probe_random_operands"), ("ones", "probe_constant_operands")):
+            tf, ghz = mfma_probe_tflops(kind)
+            line["roofline"]["mfma"][key + "_TFLOPs"] = tf
+            line["roofline"]["shader_clock_GHz"]["mfma_" + key] = ghz
     if args.all:
         others = []
         for idx in (1, 2, 3, 4):

@@ -385,9 +385,12 @@ owl_status owl_stream_read_probe(const void *src, size_t bytes, uint32_t *sink,
  * interpreted as bf16 values; their bit patterns matter: under its power limit
  * this chip sustains a lower rate on random values than on constants).  Flop =
  * n_workgroups * 8 * iters * 16 * 16384.  sink: n_workgroups * 512 floats, device.
+ * clock_ghz: optional, n_workgroups floats, device: the shader clock every
+ * workgroup ran at over its loop (shader cycles per constant-rate 100 MHz tick),
+ * which shows the throttling directly.
  */
-owl_status owl_mfma_probe(const void *src, size_t bytes, int32_t iters, float *sink, int32_t n_workgroups,
-                          void *stream);
+owl_status owl_mfma_probe(const void *src, size_t bytes, int32_t iters, float *sink, float *clock_ghz,
+                          int32_t n_workgroups, void *stream);
 
 /*
  * Measurement aid: like owl_stream_read_probe, but the buffer is read in
@@ -408,12 +411,14 @@ owl_status owl_gather_read_probe(const void *src, const int32_t *block_order, in
 owl_status owl_selftest_quad_max(const float *in64, float *out64, void *stream);
 
 /*
- * Profiling aid.  With a non-NULL device buffer of 8 * n_workgroups int64,
+ * Profiling aid.  With a non-NULL device buffer of 10 * n_workgroups int64,
  * every workgroup of the split-KV pass of later owl_verify_attn calls records
- * the GPU's constant-rate wall clock at: [0] entry, [1] page list and tree mask
- * ready, [2] first stage in LDS, [3] end of the fast loop, [4] end of the
- * careful loop, [5] partials written; [6] = its XCC id, [7] = its flat
- * workgroup index.  NULL (the default) switches recording off.  Not
+ * the GPU's constant-rate (100 MHz) wall clock at: [0] entry, [1] page list and
+ * tree mask ready, [2] first stage in LDS, [3] end of the fast loop, [4] end of
+ * the careful loop, [5] partials written; [6] = its XCC id, [7] = its flat
+ * workgroup index; [8], [9] = the shader cycle counter at [2] and [3], so that
+ * ([9] - [8]) / ([3] - [2]) / 10 is the shader clock in GHz the workgroup really
+ * ran its main loop at.  NULL (the default) switches recording off.  Not
  * thread-safe; meant for one measuring process.
  */
 owl_status owl_debug_set_timeline(long long *buffer);

@@ -109,7 +109,7 @@ def lib() -> ctypes.CDLL:
         l.owl_stream_read_probe.restype = ctypes.c_int
         l.owl_stream_read_probe.argtypes = [vp, ctypes.c_size_t, vp, i32, vp]
         l.owl_mfma_probe.restype = ctypes.c_int
-        l.owl_mfma_probe.argtypes = [vp, ctypes.c_size_t, i32, vp, i32, vp]
+        l.owl_mfma_probe.argtypes = [vp, ctypes.c_size_t, i32, vp, vp, i32, vp]
         l.owl_gather_read_probe.restype = ctypes.c_int
         l.owl_gather_read_probe.argtypes = [vp, vp, i32, vp, i32, vp]
         l.owl_debug_set_timeline.restype = ctypes.c_int
@@ -300,8 +300,9 @@ def owl_verify_attn_ragged(desc: VerifyDesc, q, k_cache, v_cache, page_table, ct
     _check(rc, "owl_verify_attn_ragged")
 
 
-def owl_mfma_probe(src, iters: int, sink, n_workgroups: int, stream: Optional[int] = None) -> None:
-    rc = lib().owl_mfma_probe(_ptr(src), src.numel() * src.element_size(), iters, _ptr(sink), n_workgroups,
+def owl_mfma_probe(src, iters: int, sink, n_workgroups: int, stream: Optional[int] = None, clock_ghz=None) -> None:
+    rc = lib().owl_mfma_probe(_ptr(src), src.numel() * src.element_size(), iters, _ptr(sink), _ptr(clock_ghz),
+                              n_workgroups,
                               _stream() if stream is None else stream)
     _check(rc, "owl_mfma_probe")
 

@@ -463,14 +463,15 @@ owl_status owl_stream_read_probe(const void *src, size_t bytes, uint32_t *sink,
     return OWL_OK;
 }
 
-owl_status owl_mfma_probe(const void *src, size_t bytes, int32_t iters, float *sink, int32_t n_workgroups,
-                          void *stream)
+owl_status owl_mfma_probe(const void *src, size_t bytes, int32_t iters, float *sink, float *clock_ghz,
+                          int32_t n_workgroups, void *stream)
 {
     if (!src || !sink || n_workgroups < 1 || iters < 1 || bytes < 16 || bytes % 16 != 0 ||
         bytes / 16 > 0x7fffffff)
         return OWL_ERR_INVALID_ARG;
     if (misaligned(src, 16)) return OWL_ERR_INVALID_ARG;
-    if (launch_mfma_probe(src, bytes, iters, sink, n_workgroups, static_cast<hipStream_t>(stream)) != hipSuccess)
+    if (launch_mfma_probe(src, bytes, iters, sink, clock_ghz, n_workgroups, static_cast<hipStream_t>(stream)) !=
+        hipSuccess)
         return OWL_ERR_HIP;
     return OWL_OK;
 }

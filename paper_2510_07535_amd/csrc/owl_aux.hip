@@ -240,7 +240,8 @@ hipError_t launch_gather_read(const void *src, const int32_t *perm, int n_blocks
 typedef float probe_f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
 
-__global__ void __launch_bounds__(512) mfma_probe_kernel(const uint4 *src, int n_vec, int iters, float *sink)
+__global__ void __launch_bounds__(512) mfma_probe_kernel(const uint4 *src, int n_vec, int iters, float *sink,
+                                                         float *clock_ghz)
 {
     uint4 a[8], b[2];
 #pragma unroll
@@ -250,6 +251,8 @@ __global__ void __launch_bounds__(512) mfma_probe_kernel(const uint4 *src, int n
     probe_f32x4 acc[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = probe_f32x4{0.f, 0.f, 0.f, 0.f};
+    // shader cycles over constant-rate (100 MHz) ticks = the clock this workgroup really ran at
+    const long long c0 = clock64(), w0 = wall_clock64();
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int i = 0; i < 16; ++i)
@@ -264,12 +267,15 @@ __global__ void __launch_bounds__(512) mfma_probe_kernel(const uint4 *src, int n
 #pragma unroll
     for (int i = 0; i < 16; ++i) s += acc[i][0] + acc[i][3];
     sink[blockIdx.x * 512 + threadIdx.x] = s;
+    const long long c1 = clock64(), w1 = wall_clock64();
+    if (clock_ghz && threadIdx.x == 0) clock_ghz[blockIdx.x] = w1 > w0 ? (float)(c1 - c0) / ((float)(w1 - w0) * 10.0f) : 0.f;
 }
 
-hipError_t launch_mfma_probe(const void *src, size_t bytes, int iters, float *sink, int n_wg, hipStream_t s)
+hipError_t launch_mfma_probe(const void *src, size_t bytes, int iters, float *sink, float *clock_ghz, int n_wg,
+                             hipStream_t s)
 {
     hipLaunchKernelGGL(mfma_probe_kernel, dim3(n_wg), dim3(512), 0, s, static_cast<const uint4 *>(src),
-                       (int)(bytes / 16), iters, sink);
+                       (int)(bytes / 16), iters, sink, clock_ghz);
     return hipGetLastError();
 }
 

@@ -34,7 +34,7 @@ struct KParams {
     int32_t row_groups;
     int64_t stride_page, stride_head, stride_token, n_pool_pages;
     float c_log2;         // scale * log2(e): scores live in the exp2 domain
-    long long *timeline;  // optional: 8 timestamps per workgroup (profiling aid), else null
+    long long *timeline;  // optional: 10 slots per workgroup (profiling aid), else null
 };
 
 // One instantiated split-KV kernel.
@@ -73,7 +73,8 @@ hipError_t launch_gather(const owl_verify_desc &d, const void *cache, const int3
                          int seq, int64_t first, int64_t n, void *dst, uint32_t *status,
                          hipStream_t s);
 
-hipError_t launch_mfma_probe(const void *src, size_t bytes, int iters, float *sink, int n_wg, hipStream_t s);
+hipError_t launch_mfma_probe(const void *src, size_t bytes, int iters, float *sink, float *clock_ghz, int n_wg,
+                             hipStream_t s);
 hipError_t launch_gather_read(const void *src, const int32_t *perm, int n_blocks, uint32_t *sink,
                               int n_wg, hipStream_t s);
 hipError_t launch_quad_max(const float *in, float *out, hipStream_t s);

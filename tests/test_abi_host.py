@@ -166,11 +166,11 @@ def test_ragged_entry_point_rejects_null_counts():
 def test_mfma_probe_rejects_before_launch():
     lib = B.lib()
     A = 0x10000
-    assert lib.owl_mfma_probe(None, 4096, 10, A, 4, None) == B.OWL_ERR_INVALID_ARG
-    assert lib.owl_mfma_probe(A, 4096, 10, None, 4, None) == B.OWL_ERR_INVALID_ARG
-    assert lib.owl_mfma_probe(A, 4100, 10, A, 4, None) == B.OWL_ERR_INVALID_ARG       # not a multiple of 16
-    assert lib.owl_mfma_probe(A, 4096, 0, A, 4, None) == B.OWL_ERR_INVALID_ARG
-    assert lib.owl_mfma_probe(A + 4, 4096, 10, A, 4, None) == B.OWL_ERR_INVALID_ARG
+    assert lib.owl_mfma_probe(None, 4096, 10, A, None, 4, None) == B.OWL_ERR_INVALID_ARG
+    assert lib.owl_mfma_probe(A, 4096, 10, None, None, 4, None) == B.OWL_ERR_INVALID_ARG
+    assert lib.owl_mfma_probe(A, 4100, 10, A, None, 4, None) == B.OWL_ERR_INVALID_ARG       # not a multiple of 16
+    assert lib.owl_mfma_probe(A, 4096, 0, A, None, 4, None) == B.OWL_ERR_INVALID_ARG
+    assert lib.owl_mfma_probe(A + 4, 4096, 10, A, None, 4, None) == B.OWL_ERR_INVALID_ARG
 
 
 # --------------------------------------------------------------------------- drafter cell

@@ -276,16 +276,20 @@ def test_measurement_aids():
     # iteration and lane: after 3 iterations sink = acc[i][0] + acc[i][3] summed over 16 accumulators
     ones = torch.ones(4096, dtype=torch.bfloat16, device="cuda")
     fs = torch.zeros(2 * 512, dtype=torch.float32, device="cuda")
-    B.owl_mfma_probe(ones, 3, fs, 2)
+    ghz = torch.zeros(2, dtype=torch.float32, device="cuda")
+    B.owl_mfma_probe(ones, 3, fs, 2, clock_ghz=ghz)
     torch.cuda.synchronize()
     assert (fs.cpu().numpy() == 16 * 2 * 3 * 32.0).all()
+    B.owl_mfma_probe(ones, 20000, fs, 2, clock_ghz=ghz)          # long enough for the 100 MHz counter to resolve
+    torch.cuda.synchronize()
+    assert ((ghz.cpu().numpy() > 0.3) & (ghz.cpu().numpy() < 3.0)).all()
 
     case = W.make_case("tl", 79, dtype=W.DT_BF16, Hq=32, Hkv=8, D=128, ctx_lens=[3000], trees=[W.random_tree(20, 4, r)])
     step = VerifyStep(case, split_tokens=512)
     step.run()
     ref = step.result().copy()
     nwg = step.plan.n_workgroups
-    tl = torch.zeros(8 * nwg, dtype=torch.int64, device="cuda")
+    tl = torch.zeros(10 * nwg, dtype=torch.int64, device="cuda")
     B.owl_debug_set_timeline(tl)
     try:
         step.run()
@@ -293,11 +297,12 @@ def test_measurement_aids():
     finally:
         B.owl_debug_set_timeline(None)
     assert np.array_equal(got, ref)                      # recording does not change the result
-    t = tl.cpu().numpy().reshape(nwg, 8)
+    t = tl.cpu().numpy().reshape(nwg, 10)
     ran = t[t[:, 0] > 0]
     assert len(ran) == 8 * ((3000 + 20 + 511) // 512)    # one workgroup per (kv head, split)
     assert (np.diff(ran[:, :6], axis=1) >= 0).all()
     assert sorted(ran[:, 7]) == sorted(set(ran[:, 7]))
+    assert (ran[:, 9] >= ran[:, 8]).all() and (ran[:, 8] > 0).all()   # shader cycles at both ends of the fast loop
 
 
 # ---------------------------------------------------------------------------
