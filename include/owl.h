@@ -99,11 +99,13 @@ typedef struct owl_verify_desc {
 /* What the library decided for a descriptor; informational (bench, tests). */
 typedef struct owl_plan {
     int32_t split_tokens;    /* tokens of the logical sequence (prefix + drafts) per split */
-                             /* for a context of max_ctx_len.  With batch == 1 and a       */
-                             /* library-chosen size, a shorter context is cut on the device */
-                             /* into max_splits shorter splits instead (never below the    */
-                             /* planner's minimum), so that the launch still fills the chip */
-    int32_t max_splits;      /* splits of the longest admissible sequence                  */
+                             /* for a context of max_ctx_len.  With a library-chosen size   */
+                             /* the kernels follow the real lengths: one shorter sequence   */
+                             /* is cut into max_splits shorter splits, a ragged batch into  */
+                             /* the shortest splits that still fill whole rounds of one     */
+                             /* workgroup per compute unit (never below the planner's       */
+                             /* minimum, never above this value)                            */
+    int32_t max_splits;      /* most splits one sequence can be cut into (sizes the partials) */
     int32_t rows_per_kv;     /* R = (Hq/Hkv) * N query rows packed against one KV stream   */
     int32_t row_tiles;       /* 16-row MFMA tiles covering R                               */
     int32_t row_groups;      /* workgroups sharing one KV split, each owning some tiles    */
@@ -415,7 +417,7 @@ owl_status owl_selftest_quad_max(const float *in64, float *out64, void *stream);
  * every workgroup of the split-KV pass of later owl_verify_attn calls records
  * the GPU's constant-rate (100 MHz) wall clock at: [0] entry, [1] page list and
  * tree mask ready, [2] first stage in LDS, [3] end of the fast loop, [4] end of
- * the careful loop, [5] partials written; [6] = its XCC id, [7] = its flat
+ * the careful loop, [5] partials written; [6] = (XCC id << 16) | CU id, [7] = its flat
  * workgroup index; [8], [9] = the shader cycle counter at [2] and [3], so that
  * ([9] - [8]) / ([3] - [2]) / 10 is the shader clock in GHz the workgroup really
  * ran its main loop at.  NULL (the default) switches recording off.  Not

@@ -57,6 +57,8 @@ struct FullPlan {
     const Variant *variant;
     size_t part_o_bytes, part_ml_bytes;
     int32_t adapt, c_min;
+    int64_t item_slots;       // adapt == 2: (sequence, split) pairs the grid has room for
+    dim3 grid;                // of the split-KV pass
 };
 
 owl_status make_plan(const owl_verify_desc *d, FullPlan *fp)
@@ -103,15 +105,31 @@ owl_status make_plan(const owl_verify_desc *d, FullPlan *fp)
     }
     if (C > kMaxSplitTokens) C = kMaxSplitTokens;
     if (C < kSplitQuantum) C = kSplitQuantum;
-    const int64_t max_splits = (T + C - 1) / C;
+    int64_t max_splits = (T + C - 1) / C;
     // One sequence and a library-chosen split size: the kernels cut a context
     // shorter than max_ctx_len into the same number of splits (never below the
     // minimum used above), so the launch still fills the chip.
-    fp->adapt = d->split_tokens == 0 && d->batch == 1;
+    // A batch with a library-chosen size: the kernels shrink the split so that the real
+    // (ragged) lengths fill whole rounds of workgroups (batch_split_tokens).  Going from
+    // k-and-a-bit rounds to k + 1 full ones never needs less than half the planned size,
+    // so the grid and the partials are sized for splits of C / 2.
+    fp->adapt = d->split_tokens != 0 ? 0 : (d->batch == 1 ? 1 : 2);
     {
         int64_t cmin = align_up((size_t)(8 * R), kSplitQuantum);
         if (cmin < 256) cmin = 256;
         fp->c_min = (int32_t)(cmin < C ? cmin : C);
+    }
+    fp->item_slots = (int64_t)d->batch * max_splits;
+    if (fp->adapt == 2) {
+        // The device never asks for more pairs than the planned size gives at full length,
+        // rounded up to whole rounds, plus one per sequence for rounding: that many slots,
+        // numbered densely, are launched; a single sequence may use up to twice its share.
+        const int64_t streams = (int64_t)d->n_kv_heads * rgs;
+        fp->item_slots = (int64_t)d->batch * max_splits + (device_cus() + streams - 1) / streams + d->batch;
+        int64_t c_floor = align_up((size_t)(C / 2), kSplitQuantum);
+        if (c_floor < fp->c_min) c_floor = fp->c_min;
+        max_splits = (T + c_floor - 1) / c_floor;
+        if (fp->item_slots > (int64_t)d->batch * max_splits) fp->item_slots = (int64_t)d->batch * max_splits;
     }
 
     const size_t slots = (size_t)d->batch * d->n_kv_heads * (size_t)max_splits * RT;
@@ -126,8 +144,15 @@ owl_status make_plan(const owl_verify_desc *d, FullPlan *fp)
     pl.row_groups = rgs;
     pl.tiles_per_wave = tpw;
     pl.kernel_variant = variant_index(v);
-    pl.n_workgroups = (int32_t)(max_splits * d->n_kv_heads * rgs * d->batch);
-    pl.workspace_bytes = fp->part_o_bytes + fp->part_ml_bytes;
+    // KV heads vary fastest (see the kernel's block-index comment); for a batch with a library-chosen
+    // split size (y, z) merely number its (sequence, split) pairs densely
+    fp->grid = dim3(d->n_kv_heads * rgs, (unsigned)max_splits, d->batch);
+    if (fp->adapt == 2) {
+        const int64_t per_z = fp->item_slots < 32768 ? fp->item_slots : 32768;
+        fp->grid = dim3(d->n_kv_heads * rgs, (unsigned)per_z, (unsigned)((fp->item_slots + per_z - 1) / per_z));
+    }
+    pl.n_workgroups = (int32_t)((int64_t)fp->grid.x * fp->grid.y * fp->grid.z);
+    pl.workspace_bytes = fp->part_o_bytes + fp->part_ml_bytes + 256;    // + the derived split size
     return OWL_OK;
 }
 
@@ -252,6 +277,8 @@ static owl_status verify_impl(const owl_verify_desc *desc, const void *q, const 
     p.max_pages = desc->max_pages_per_seq; p.max_ctx_len = desc->max_ctx_len;
     p.C = fp.pub.split_tokens; p.max_splits = fp.pub.max_splits;
     p.adapt = fp.adapt; p.c_min = fp.c_min;
+    p.n_cu = device_cus();
+    p.dev_c = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + fp.part_o_bytes + fp.part_ml_bytes);
     p.RT = fp.pub.row_tiles; p.row_groups = fp.pub.row_groups;
     p.stride_page = desc->kv_stride_page; p.stride_head = desc->kv_stride_head;
     p.stride_token = desc->kv_stride_token; p.n_pool_pages = desc->n_pool_pages;
@@ -259,7 +286,8 @@ static owl_status verify_impl(const owl_verify_desc *desc, const void *q, const 
     p.timeline = g_timeline;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    dim3 grid(p.Hkv * p.row_groups, p.max_splits, p.B);   // heads fastest: see the kernel's block-index comment
+    p.item_slots = (int32_t)fp.item_slots;
+    const dim3 grid = fp.grid;
     if (phases & OWL_PHASE_SPLIT) {
         fp.variant->launch(p, grid, s);
         if (hipGetLastError() != hipSuccess) return OWL_ERR_HIP;

@@ -29,8 +29,13 @@ __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
 
     const int L = load_ctx_len(p.ctx_lens, b, p.max_ctx_len, nullptr);
     const int Nb = load_n_draft(p.n_draft_seq, b, p.N, nullptr);
-    const int C = split_tokens_for(p, L + Nb);
-    const int ns = Nb == 0 ? 0 : (L + Nb + C - 1) / C;            // a sequence without drafts wrote no partials
+    int C = split_tokens_for(p, L + Nb);
+    if (p.adapt == 2) {                                           // what the split-KV pass derived for this batch;
+        C = *p.dev_c;                                             // forced into range should that pass not have run
+        C = min(max(C / kSplitQuantum, 1) * kSplitQuantum, p.C);
+    }
+    int ns = Nb == 0 ? 0 : (L + Nb + C - 1) / C;                  // a sequence without drafts wrote no partials
+    ns = min(ns, p.max_splits);
     const size_t slot0 = (((size_t)b * p.Hkv + g) * p.max_splits) * p.RT + tg;
 
     float mw = -INFINITY, lw = 0.f;

@@ -41,11 +41,126 @@ __device__ __forceinline__ int load_n_draft(const int32_t *n_draft_seq, int b, i
 // Never above p.C, never below the planner's minimum, a multiple of the stage.
 __device__ __forceinline__ int split_tokens_for(const KParams &p, int T)
 {
-    if (!p.adapt) return p.C;
+    if (p.adapt != 1) return p.C;
     int C = (T + p.max_splits - 1) / p.max_splits;
     C = (C + kSplitQuantum - 1) / kSplitQuantum * kSplitQuantum;
     C = max(C, p.c_min);
     return min(C, p.C);
+}
+
+// Cached rows of sequence b that the pass has to scan: 0 for a sequence without drafts.
+__device__ __forceinline__ int seq_tokens(const KParams &p, int b)
+{
+    int L = p.ctx_lens[b];
+    L = L < 0 ? 0 : (L > p.max_ctx_len ? p.max_ctx_len : L);        // flagged where the sequence is processed
+    int n = p.n_draft_seq ? p.n_draft_seq[b] : p.N;
+    n = n < 0 ? 0 : (n > p.N ? p.N : n);
+    return n == 0 ? 0 : L + n;
+}
+
+// Sum / maximum over lanes [0, n) of a wavefront, as scalars (n uniform, <= 64).
+__device__ __forceinline__ int lanes_sum(int v, int n)
+{
+    int s = 0;
+    for (int l = 0; l < n; ++l) s += __builtin_amdgcn_readlane(v, l);
+    return s;
+}
+__device__ __forceinline__ int lanes_max(int v, int n)
+{
+    int m = 0;
+    for (int l = 0; l < n; ++l) m = max(m, __builtin_amdgcn_readlane(v, l));
+    return m;
+}
+
+// Split size for a batch (adapt == 2).  The host plans for B sequences of the
+// longest admissible length; a real batch is ragged, and with one workgroup per
+// compute unit at a time a launch of, say, 1.4 rounds leaves most of the chip
+// idle for its last round.  Every wavefront derives, from the actual lengths,
+// about the smallest split size (a multiple of the stage, within the planner's
+// bounds and the launched grid) whose workgroup count still fits the whole
+// number of rounds that the planned size needs: the rounds come out full and as
+// short as they can be.  All lanes of the calling wavefront, and every wavefront
+// of the launch, get the same value: it depends only on p and the two length
+// arrays, and the combine reads the value the split-KV pass stored.
+//
+// The search runs across lanes: lane l prices one candidate size against all
+// sequences (their lengths travel as scalars), a ballot picks the first
+// candidate that fits, a second pass refines between it and its neighbour.
+// Workgroup counts of candidates are formed in float: a count that is off by
+// one moves the choice by a stage, never the validity of the result.
+__device__ __forceinline__ int batch_split_tokens(const KParams &p)
+{
+    const int lane = threadIdx.x & 63;
+    const int streams = p.Hkv * p.row_groups;        // workgroups per split
+    // sequence lengths: sequence b < 64 sits in lane b; further ones are re-read (uniform loads)
+    const int t_lane = lane < p.B ? seq_tokens(p, lane) : 0;
+    const int n_lane = min(p.B, 64);
+    auto tokens_of = [&](int b) { return b < 64 ? __builtin_amdgcn_readlane(t_lane, b) : seq_tokens(p, b); };
+
+    int max_t = lanes_max(t_lane, n_lane);
+    for (int b = 64; b < p.B; ++b) max_t = max(max_t, seq_tokens(p, b));
+
+    const int hi = p.C / kSplitQuantum;
+    int lo = ((max_t + p.max_splits - 1) / p.max_splits + kSplitQuantum - 1) / kSplitQuantum;   // the grid has max_splits
+    lo = min(max(max(lo, p.c_min / kSplitQuantum), 1), hi);
+
+    // whole rounds the planned size needs (exact)
+    int at_hi = lanes_sum((t_lane + p.C - 1) / p.C, n_lane);
+    for (int b = 64; b < p.B; ++b) at_hi += (seq_tokens(p, b) + p.C - 1) / p.C;
+    const int rounds = (at_hi * streams + p.n_cu - 1) / p.n_cu;
+    const float budget = (float)(rounds * p.n_cu) / (float)streams + 0.5f;      // splits that fit
+
+    // first candidate q0 + lane * step (capped at hi) whose split count fits; -1 if none does
+    auto first_fit = [&](int q0, int step) {
+        const int q = min(q0 + lane * step, hi);
+        const float rc = 1.0f / (float)(q * kSplitQuantum);
+        float n = 0.f;
+        for (int b = 0; b < p.B; ++b) n += ceilf((float)tokens_of(b) * rc);
+        const unsigned long long ok = __ballot(n <= budget);
+        return ok ? (int)__ffsll((long long)ok) - 1 : -1;
+    };
+    if (hi == lo) return hi * kSplitQuantum;
+    const int step = (hi - lo + 62) / 63;            // lane 63 reaches hi; <= 5 for the largest split the planner allows
+    const int l1 = first_fit(lo, step);
+    if (l1 < 0) return hi * kSplitQuantum;
+    int q = lo + l1 * step;
+    if (l1 > 0 && step > 1) {                        // refine between the last misfit and the first fit
+        const int q1 = lo + (l1 - 1) * step + 1;
+        const int l2 = first_fit(q1, 1);
+        if (l2 >= 0) q = q1 + l2;
+    }
+    const int C = min(q, hi) * kSplitQuantum;
+    // the launched grid has room for what the bounds above allow; should the float counts ever
+    // have let more through, the planned size (which always fits) is used instead
+    int total = lanes_sum((t_lane + C - 1) / C, n_lane);
+    for (int b = 64; b < p.B; ++b) total += (seq_tokens(p, b) + C - 1) / C;
+    return total <= p.item_slots ? C : p.C;
+}
+
+// The (sequence, split) pair that work item `id` of a batch stands for when the
+// items of all sequences are numbered densely, sequence by sequence, with splits
+// of C tokens: workgroups that have something to do then come first in launch
+// order and the surplus of the grid (sized for the worst case) trails behind,
+// instead of being dispatched in between and holding up the ones behind them.
+// Wave-uniform; false if id is beyond the last item.
+__device__ __forceinline__ bool batch_item(const KParams &p, int C, int id, int *b_out, int *c_out)
+{
+    const int lane = threadIdx.x & 63;
+    int base = 0;
+    for (int b0 = 0; b0 < p.B; b0 += 64) {
+        const int n = b0 + lane < p.B ? (seq_tokens(p, b0 + lane) + C - 1) / C : 0;
+        const int n_lane = min(p.B - b0, 64);
+        for (int l = 0; l < n_lane; ++l) {           // scalar walk over the chunk's sequences
+            const int nl = __builtin_amdgcn_readlane(n, l);
+            if (id < base + nl) {
+                *b_out = b0 + l;
+                *c_out = id - base;
+                return true;
+            }
+            base += nl;
+        }
+    }
+    return false;
 }
 
 // Physical page of logical page lp of sequence b; an id outside the pool (or a

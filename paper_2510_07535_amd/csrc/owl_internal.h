@@ -27,7 +27,10 @@ struct KParams {
     int32_t B, N, Hq, Hkv, G, R;
     int32_t max_pages, max_ctx_len;
     int32_t C;            // tokens per split (an upper bound when `adapt` is set)
-    int32_t adapt;        // one sequence, library-chosen splits: the split size follows the actual length
+    int32_t adapt;        // library-chosen splits follow the actual lengths: 1 = the one sequence's, 2 = the batch's
+    int32_t n_cu;         // compute units: the workgroup slots of one round
+    int32_t item_slots;   // adapt == 2: (sequence, split) pairs the launched grid has room for
+    int32_t *dev_c;       // adapt == 2: the split size the split-KV pass derived, for the combine
     int32_t c_min;        // smallest split size the planner allows
     int32_t max_splits;
     int32_t RT;           // row tiles covering R

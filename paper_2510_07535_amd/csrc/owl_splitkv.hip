@@ -197,12 +197,12 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     // Workgroups go to the chip's eight XCDs round-robin in launch order, whether or not
     // they have work.  KV heads (all with the same amount of work) vary fastest, so that
     // splits that do not exist for a short sequence do not leave whole XCDs idle.
-    const int c = blockIdx.y;
+    int c = blockIdx.y;
     // Row groups that share a KV split (more than 24 row tiles) sit Hkv apart in x: with 8 KV
     // heads they land on the same XCD at about the same time, and the second reads the split
     // from that XCD's L2.
     const int g = blockIdx.x % p.Hkv, rg = blockIdx.x / p.Hkv;
-    const int b = blockIdx.z;
+    int b = blockIdx.z;
 
     // optional timeline of this workgroup (profiling aid)
     long long *tl = nullptr;
@@ -212,7 +212,8 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
         if (tid == 0) {
             tl[0] = wall_clock64();
             tl[1] = tl[2] = tl[3] = tl[4] = tl[5] = tl[8] = tl[9] = 0;
-            tl[6] = __smid();
+            // XCC_ID register (bits 3:0) above the shader-engine / CU id: one value per compute unit
+            tl[6] = ((long long)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 15) << 16) | __smid();
             tl[7] = flat;
         }
     }
@@ -228,6 +229,12 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     // first, so that all of the kernel's set-up reads are in flight together:
     // raw page-table entries of this split's window, the parent array, Q ----
     int C = p.C;                                      // revised below once the context length is known
+    if (p.adapt == 2) {                               // a batch: the split size follows all its lengths
+        C = batch_split_tokens(p);
+        if (tid == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) *p.dev_c = C;
+        // (y, z) is only a number here: the items that exist are the first ones in launch order
+        if (!batch_item(p, C, blockIdx.y + gridDim.y * blockIdx.z, &b, &c)) return;
+    }
     int pos0 = c * C;
     // drafted tokens of this sequence (a batch may mix tree sizes): rows of nodes >= Nb are
     // idle, their K/V rows are not part of the sequence, and the combine writes zeros for them
@@ -281,7 +288,7 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
 
     const int L = load_ctx_len(p.ctx_lens, b, p.max_ctx_len, p.dev_status);
     const int Ttot = L + Nb;
-    if (split_tokens_for(p, Ttot) != C) {           // uniform: a context shorter than planned for
+    if (p.adapt == 1 && split_tokens_for(p, Ttot) != C) {   // uniform: a context shorter than planned for
         C = split_tokens_for(p, Ttot);
         pos0 = c * C;
         request_pages();                            // the window moved: one more round trip

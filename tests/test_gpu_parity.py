@@ -365,6 +365,48 @@ def test_ragged_draft_counts(oracle_mod, dtype, N, G, counts):
             assert (got[b, n:] == 0).all()
 
 
+@pytest.mark.parametrize("name,ctx,Hkv", [
+    ("one long, many short", [9000] + [300] * 15, 8),            # under-filled launch: the long one is cut finer
+    ("more sequences than lanes", None, 2),                      # 70 sequences: the second 64-chunk of the search
+    ("equal lengths", [2000] * 12, 4),
+    ("all empty prefixes", [0] * 5, 2),
+])
+def test_batch_split_follows_the_lengths(oracle_mod, name, ctx, Hkv):
+    """A batch with a library-chosen split size: the kernels derive the split size from the
+    actual lengths and number the (sequence, split) pairs densely; the result must not care,
+    and the planned grid must hold every pair (an unserved pair would leave a row's partials
+    unwritten and show as a mismatch)."""
+    r = _rng(4242)
+    if ctx is None:
+        ctx = [int(x) for x in r.integers(0, 400, size=70)]
+        ctx[3] = ctx[66] = 0
+        ctx[69] = 1500
+    n = 5
+    case = W.make_case("batchsplit", 77, dtype=W.DT_BF16, Hq=4 * Hkv, Hkv=Hkv, D=128, ctx_lens=ctx,
+                       trees=[W.random_tree(n, 3, r) for _ in ctx])
+    want = oracle_mod.verify_attn_case(case)
+    got, step = _run(case)
+    assert_close(got, want, case.dtype, name)
+    # announced longer than anything present: the plan (grid, partials) is for 65536, the lengths are not
+    import dataclasses
+    cols = (65536 + n + 15) // 16                        # the page table has to cover the planned length
+    table = np.zeros((case.B, cols), dtype=np.int32)
+    table[:, :case.page_table.shape[1]] = case.page_table
+    wide = dataclasses.replace(case, page_table=table, max_pages_per_seq=cols)
+    got2, step2 = _run(wide, max_ctx_len=65536)
+    assert_close(got2, want, case.dtype, name + " (planned for 65536)")
+    if len(ctx) <= 16:                                   # with per-sequence draft counts on top
+        counts = [n if b % 3 else max(0, n - 2 - b % 2) for b in range(len(ctx))]
+        counts[0] = 0 if len(ctx) > 1 else n
+        want3 = oracle_mod.verify_attn_ragged_case(case, counts)
+        nd = torch.tensor(counts, dtype=torch.int32, device=step.device)
+        B.owl_verify_attn_ragged(step.desc, step.q, step.k, step.v, step.page_table, step.ctx_lens,
+                                 step.tree_parent, nd, step.out, step.workspace, step.status)
+        got3 = step.result()
+        assert step.dev_status() == 0
+        assert_close(got3, want3, case.dtype, name + " (ragged counts)")
+
+
 def test_ragged_flags_bad_counts():
     case = W.make_case("ragged_bad", 77, dtype=W.DT_BF16, Hq=8, Hkv=2, D=128, ctx_lens=[300, 200],
                        trees=[W.chain_tree(5) for _ in range(2)])
