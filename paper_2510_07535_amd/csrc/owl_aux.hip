@@ -42,23 +42,37 @@ __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
     float4 acc[UPW];
 #pragma unroll
     for (int u = 0; u < UPW; ++u) acc[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s = w; s < ns; s += 4) {
-        const size_t slot = slot0 + (size_t)s * p.RT;
-        const float ms = p.part_ml[slot * 32 + j];
-        const float ls = p.part_ml[slot * 32 + 16 + j];
-        const float4 *po = reinterpret_cast<const float4 *>(p.part_o) + slot * (size_t)(NT * 64) + lane;
-        float4 x[UPW];
+    // The merge is a chain (each split rescales the running sums), the loads are not: the
+    // partials of kInFlight splits are requested together, so that a wavefront pays the
+    // memory latency once per batch rather than once per split.
+    constexpr int kInFlight = 4;
+    for (int s0 = w; s0 < ns; s0 += 4 * kInFlight) {
+        float ms[kInFlight], ls[kInFlight];
+        float4 x[kInFlight][UPW];
 #pragma unroll
-        for (int u = 0; u < UPW; ++u) x[u] = po[(u0 + u) * 64];
-        const float mn = fmaxf(mw, ms);
-        const float a = __builtin_amdgcn_exp2f(mw - mn);     // 0 on the first round (mw = -inf)
-        const float c = __builtin_amdgcn_exp2f(ms - mn);
-        mw = mn;
-        lw = lw * a + ls * c;
+        for (int k = 0; k < kInFlight; ++k) {
+            const int s = min(s0 + 4 * k, ns - 1);           // past the end: re-read the last split, not merged
+            const size_t slot = slot0 + (size_t)s * p.RT;
+            ms[k] = p.part_ml[slot * 32 + j];
+            ls[k] = p.part_ml[slot * 32 + 16 + j];
+            const float4 *po = reinterpret_cast<const float4 *>(p.part_o) + slot * (size_t)(NT * 64) + lane;
 #pragma unroll
-        for (int u = 0; u < UPW; ++u) {
-            acc[u].x = acc[u].x * a + x[u].x * c; acc[u].y = acc[u].y * a + x[u].y * c;
-            acc[u].z = acc[u].z * a + x[u].z * c; acc[u].w = acc[u].w * a + x[u].w * c;
+            for (int u = 0; u < UPW; ++u) x[k][u] = po[(u0 + u) * 64];
+        }
+#pragma unroll
+        for (int k = 0; k < kInFlight; ++k) {
+            if (s0 + 4 * k < ns) {                           // uniform over the wavefront
+                const float mn = fmaxf(mw, ms[k]);
+                const float a = __builtin_amdgcn_exp2f(mw - mn);     // 0 on the first round (mw = -inf)
+                const float c = __builtin_amdgcn_exp2f(ms[k] - mn);
+                mw = mn;
+                lw = lw * a + ls[k] * c;
+#pragma unroll
+                for (int u = 0; u < UPW; ++u) {
+                    acc[u].x = acc[u].x * a + x[k][u].x * c; acc[u].y = acc[u].y * a + x[k][u].y * c;
+                    acc[u].z = acc[u].z * a + x[k][u].z * c; acc[u].w = acc[u].w * a + x[k][u].w * c;
+                }
+            }
         }
     }
     __shared__ float4 s_acc[4][UPW][64];
