@@ -387,6 +387,14 @@ def test_batch_split_follows_the_lengths(oracle_mod, name, ctx, Hkv):
     want = oracle_mod.verify_attn_case(case)
     got, step = _run(case)
     assert_close(got, want, case.dtype, name)
+    # the split size the kernels derived sits in the last 256 bytes of the workspace: a multiple of the
+    # 64-token stage, at most the planned size, and its (sequence, split) pairs fit the launched grid
+    c_dev = int(step.workspace[-256:-252].view(torch.int32).item())
+    plan = step.plan
+    assert c_dev % 64 == 0 and 64 <= c_dev <= plan.split_tokens
+    pairs = sum(-(-(int(L) + n) // c_dev) for L in ctx)
+    assert pairs * Hkv * plan.row_groups <= plan.n_workgroups
+    assert all(-(-(int(L) + n) // c_dev) <= plan.max_splits for L in ctx)
     # announced longer than anything present: the plan (grid, partials) is for 65536, the lengths are not
     import dataclasses
     cols = (65536 + n + 15) // 16                        # the page table has to cover the planned length
