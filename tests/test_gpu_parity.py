@@ -415,6 +415,47 @@ def test_batch_split_follows_the_lengths(oracle_mod, name, ctx, Hkv):
         assert_close(got3, want3, case.dtype, name + " (ragged counts)")
 
 
+def test_graph_capture_replays_match_eager(oracle_mod):
+    """No entry point allocates, clears memory or synchronises, so a verify step can be captured
+    in a HIP graph.  The graph is replayed several times with new queries and lengths in the
+    same buffers, with eager work and synchronisations in between; every replay must equal the
+    eager result on the same inputs."""
+    r = _rng(606)
+    ctx = [1500, 40, 700]
+    case = W.make_case("graph", 61, dtype=W.DT_BF16, Hq=16, Hkv=4, D=128, ctx_lens=ctx,
+                       trees=[W.random_tree(12, 4, r) for _ in ctx])
+    step = VerifyStep(case)
+    step.run()                                            # warm-up outside the capture (one-time kernel attributes)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step.run()
+    torch.cuda.synchronize()
+    q0 = step.q.clone()
+    for rep in range(4):
+        if rep:                                           # new inputs in place: scaled queries, shorter contexts
+            step.q.copy_((q0.view(torch.bfloat16).float() * (1.0 + 0.25 * rep)).to(torch.bfloat16).view(torch.int16))
+            step.ctx_lens.copy_(torch.tensor([1500 - 100 * rep, 40, 700 - 300 * (rep % 2)], dtype=torch.int32))
+        torch.cuda.synchronize()
+        step.out.fill_(float("nan"))
+        graph.replay()
+        got = step.result().copy()
+        step.out.fill_(float("nan"))
+        step.run()                                        # eager, same buffers
+        want = step.result().copy()
+        assert step.dev_status() == 0
+        assert np.array_equal(got, want), f"replay {rep}"
+    # and the first replay's inputs were the seeded case: against the oracle too
+    step.q.copy_(q0)
+    step.ctx_lens.copy_(torch.tensor(ctx, dtype=torch.int32))
+    torch.cuda.synchronize()
+    graph.replay()
+    assert_close(step.result(), oracle_mod.verify_attn_case(case), case.dtype, "graph replay")
+
+
 def test_ragged_flags_bad_counts():
     case = W.make_case("ragged_bad", 77, dtype=W.DT_BF16, Hq=8, Hkv=2, D=128, ctx_lens=[300, 200],
                        trees=[W.chain_tree(5) for _ in range(2)])
