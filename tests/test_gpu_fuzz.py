@@ -1,0 +1,56 @@
+"""Seeded random sweep of the verify attention against the oracle: shapes, layouts,
+paging, batch sizes, tree shapes, split sizes and storage types drawn at random,
+every output element compared.  Needs an MI355X (-m gpu); calls go through the C ABI."""
+import numpy as np
+import pytest
+
+from paper_2510_07535_amd import workloads as W
+from paper_2510_07535_amd.runner import VerifyStep
+from util import assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+def _draw(seed):
+    r = np.random.Generator(np.random.Philox(key=10_000 + seed))
+    dtype = [W.DT_BF16, W.DT_BF16, W.DT_F16, W.DT_F32][int(r.integers(4))]
+    D = 64 if dtype == W.DT_F32 else int(r.choice([64, 128]))
+    Hkv = int(r.choice([1, 2, 4, 8]))
+    G = int(r.choice([1, 2, 4, 8]))
+    N = int(r.choice([1, 2, 5, 13, 26, 40, 60, 64]))
+    if dtype == W.DT_F32:
+        N = min(N, 13)
+        G = min(G, 4)
+    B = int(r.choice([1, 1, 2, 3, 7]))
+    top = int(r.choice([0, 17, 300, 1100, 2600]))
+    ctx = [int(r.integers(0, top + 1)) for _ in range(B)]
+    kind = int(r.integers(3))
+    trees = []
+    for _ in range(B):
+        if kind == 0 or N == 1:
+            trees.append(W.chain_tree(N))
+        elif kind == 1:
+            trees.append(W.random_tree(N, int(r.integers(2, 9)), r))
+        else:
+            trees.append(W.random_tree(N, None, r))
+    paged = bool(r.integers(2)) or B > 1
+    head_major = bool(r.integers(2))
+    split = int(r.choice([0, 0, 64, 192, 448, 1024]))
+    outliers = 0.05 if r.integers(4) == 0 else 0.0
+    case = W.make_case(f"fuzz{seed}", 500 + seed, dtype=dtype, Hq=Hkv * G, Hkv=Hkv, D=D, ctx_lens=ctx, trees=trees,
+                       paged=paged, head_major=head_major, outlier_frac=outliers,
+                       spare_pages=int(r.integers(0, 4)))
+    return case, split
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_shape_matches_oracle(oracle_mod, seed):
+    case, split = _draw(seed)
+    step = VerifyStep(case, split_tokens=split)
+    step.run()
+    got = step.result()
+    assert step.dev_status() == 0
+    want = oracle_mod.verify_attn_case(case)
+    what = (f"seed {seed}: dtype {case.dtype} B {case.B} N {case.N} Hq {case.Hq} Hkv {case.Hkv} D {case.D} "
+            f"ctx {case.ctx_lens.tolist()} split {split} plan {step.plan.as_dict()}")
+    assert_close(got, want, case.dtype, what)
