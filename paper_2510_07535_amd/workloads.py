@@ -86,6 +86,8 @@ def node_depths(parent: Sequence[int]) -> np.ndarray:
 def random_tree(n: int, max_depth: Optional[int], rng: np.random.Generator) -> np.ndarray:
     """Node 0 is the root; every later node draws its parent uniformly from
     the earlier nodes whose depth is below ``max_depth`` (root depth = 1)."""
+    if max_depth is not None and max_depth < 2 and n > 1:
+        raise ValueError("a tree of several nodes under one root needs max_depth >= 2")
     parent = np.full(n, -1, dtype=np.int32)
     depth = np.zeros(n, dtype=np.int32)
     depth[0] = 1
