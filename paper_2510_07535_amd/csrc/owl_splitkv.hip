@@ -240,6 +240,10 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     // idle, their K/V rows are not part of the sequence, and the combine writes zeros for them
     const int Nb = load_n_draft(p.n_draft_seq, b, p.N, p.dev_status);
     if (Nb == 0) return;
+    // The context length is requested before everything else: vector loads complete in
+    // order, so asked for after the query fragments it would only arrive behind them
+    // (2.4 us later with 15-20 row tiles), and the whole prologue hangs on it.
+    const int L = load_ctx_len(p.ctx_lens, b, p.max_ctx_len, p.dev_status);
     int raw_page[kMaxPagesPerSplit / kThreads];
     auto request_pages = [&]() {
         const int win_pages = C / kPage;             // pages a full split spans (<= kMaxPagesPerSplit)
@@ -260,6 +264,10 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     float qs[TPW][kF32 ? QREGS : 1];
     int irow[TPW];
     int my_nt = 0;
+    // Requested only after the first K/V stage (below): the query fragments of all workgroups of
+    // a KV head are the same few L2 lines, they take ~2 us to come in with 15-20 row tiles, and
+    // vector loads complete in order, so the first stage's DMA would queue up behind them.
+    auto load_queries = [&]() {
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
         const int tg = rg * (WR * TPW) + t * WR + wr;
@@ -284,9 +292,8 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
         }
     }
     my_nt = __builtin_amdgcn_readfirstlane(my_nt);
+    };
 
-
-    const int L = load_ctx_len(p.ctx_lens, b, p.max_ctx_len, p.dev_status);
     const int Ttot = L + Nb;
     if (p.adapt == 1 && split_tokens_for(p, Ttot) != C) {   // uniform: a context shorter than planned for
         C = split_tokens_for(p, Ttot);
@@ -871,8 +878,10 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     // an fp16 P overflows 12 above it (and the redo is then the price).  fp32 is
     // the small correctness shape and has no fast loop.
     constexpr bool kHasFast = !kF32;
+    issue_stage(0);                                   // nstages >= 1: the split exists
+    load_queries();
     for (int pass = 0; pass < 2; ++pass) {
-        issued = 0;
+        issued = pass == 0 ? 1 : 0;                   // the redo pass starts over
         for (; issued < NS - 1 && issued < nstages; ++issued) issue_stage(issued);
         int n_fast = 0;
         if (kHasFast && pass == 0) n_fast = max(0, min(nstages, (L - pos0) / SK));
