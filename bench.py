@@ -56,6 +56,8 @@ def parse():
                     help="storage type of q/K/V (the configurations list bf16; f16 is the paper's type)")
     ap.add_argument("--drafter", action="store_true",
                     help="also time the drafter's recurrent cell (reported under 'drafter_cell'; implied by --all)")
+    ap.add_argument("--draft-sweep", action="store_true",
+                    help="also time a 64K-context step for 1..60 drafted tokens (reported under 'draft_count_sweep')")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
     return ap.parse_args()
@@ -325,6 +327,26 @@ def bench_drafter(steps=60, with_cpu=True):
     return out
 
 
+def bench_draft_sweep(ctx=65536, counts=(1, 4, 8, 16, 24, 32, 48, 60)):
+    """Cost of one verify step against the number of drafted tokens: 8B head shapes, one
+    sequence of `ctx` cached tokens, chains up to 8 tokens and depth-6 trees beyond."""
+    import numpy as np
+    import torch
+    from paper_2510_07535_amd import workloads as W
+    rng = np.random.Generator(np.random.Philox(key=3))
+    out = []
+    for n in counts:
+        tree = W.chain_tree(n) if n <= 8 else W.random_tree(n, 6, rng)
+        case = W.make_case(f"sweep_n{n}", 9, dtype=W.DT_BF16, Hq=32, Hkv=8, D=128, ctx_lens=[ctx], trees=[tree])
+        rot = Rotating(case)
+        sec = rot.time_steps(150, 20)
+        out.append({"n_draft": n, "rows_per_kv": rot.step.plan.rows_per_kv, "ctx": ctx, "us_per_step": sec * 1e6,
+                    "GBps": rot.kv_bytes / sec / 1e9})
+        del rot
+        torch.cuda.empty_cache()
+    return out
+
+
 def bench_config(idx, args, want_detail):
     from paper_2510_07535_amd import workloads as W
     case = W.make_config(idx, dtype={"bf16": W.DT_BF16, "f16": W.DT_F16}[args.dtype])
@@ -403,6 +425,8 @@ def main():
             others.append(r)
         line["others"] = others
         line["step_kernels"] = bench_steps()
+    if args.draft_sweep:
+        line["draft_count_sweep"] = bench_draft_sweep()
     if args.all or args.drafter:
         line["drafter_cell"] = bench_drafter(with_cpu=not args.no_cpu_baseline)
     if not args.no_cpu_baseline:
