@@ -431,6 +431,11 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     };
 
     // ---- fast step: no mask, fixed reference m, accumulators touched by MFMA only ----
+    // fp16 storage: a workgroup whose first step shows a wide spread of scores takes the plain loop
+    // with a guarded reference (see fast_sx) instead of the frozen one; the choice only affects
+    // speed (a frozen reference that overflows is caught by the row sums and the split redone)
+    constexpr bool kGuard = std::is_same<T, _Float16>::value;
+    bool use_guard = false;
     // p = 2^(x - m) is exact in relative terms whatever m is; with m frozen at
     // the first step's row maximum, p overflows only if a later score exceeds
     // it by more than ~100 (log2 units), which the row sum exposes afterwards.
@@ -438,8 +443,9 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     // the V^T fragments already in registers (fast_pv), so that the stage loop
     // can put a barrier between them.
     auto fast_sx = [&](const unsigned char *Kb, const unsigned char *Vb, uint4 (&pf)[TPW], uint4 (&vf)[NT],
-                       auto ntag) {
+                       auto ntag, auto gtag) {
         constexpr int NA = decltype(ntag)::value;    // tiles this wave really owns
+        constexpr bool kGuarded = decltype(gtag)::value;
         if constexpr (!kF32 && NA > 0) {
             // The score -> softmax -> P chain is the latency-critical part of a step; O += V^T P
             // is throughput work without dependents.  Raising this wave's priority for the
@@ -455,6 +461,22 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
                 for (int kk = 0; kk < KQ; ++kk) {
                     s0 = mfma16<T>(kf[0][kk], qf[t][kk], s0);
                     s1 = mfma16<T>(kf[1][kk], qf[t][kk], s1);
+                }
+                if constexpr (kGuarded) {
+                    // fp16 holds 2^(x - m) only up to 2^16.  The reference stays frozen as long as no
+                    // score of the step comes within 2^5 of that; a row that does moves its reference
+                    // 4 above the offender and rescales its accumulators (rare; uniform branch).
+                    const float tm = fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
+                                           fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3])));
+                    // detection needs no cross-lane step: any lane's own keys can raise the alarm
+                    if (__builtin_amdgcn_ballot_w64(__builtin_fmaf(tm, p.c_log2, -m[t]) > 11.0f) != 0) {
+                        const float sc = quad_column_max(tm) * p.c_log2;
+                        const float mn = sc > m[t] + 11.0f ? sc + 4.0f : m[t];
+                        const float alpha = fast_exp2(m[t] - mn);
+                        m[t] = mn;
+#pragma unroll
+                        for (int u = 0; u <= NT; ++u) O[t][u] *= alpha;
+                    }
                 }
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
@@ -762,7 +784,7 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     // ring slot is free all the same) across the barrier.  After every barrier
     // the two waves of a SIMD are then half a step apart, and one's matrix work
     // overlaps the other's vector work.
-    auto run_fast_n = [&](int n_fast, auto ntag) {
+    auto run_fast_n = [&](int n_fast, auto ntag, auto gtag) {
         if constexpr (!kF32) {
             const bool late = wave >= kWaves / 2;
             auto kptr = [&](int s, int ks) -> const unsigned char * {
@@ -784,16 +806,16 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
                         admit(s);
                         if (late) fast_pv(pf, vf, ntag);         // late waves carry it over
                     }
-                    fast_sx(kptr(s, 0), kptr(s, 0) + VREG, pf, vf, ntag);
+                    fast_sx(kptr(s, 0), kptr(s, 0) + VREG, pf, vf, ntag, gtag);
                     fast_pv(pf, vf, ntag);
-                    fast_sx(kptr(s, 1), kptr(s, 1) + VREG, pf, vf, ntag);
+                    fast_sx(kptr(s, 1), kptr(s, 1) + VREG, pf, vf, ntag, gtag);
                 } else {
                     if (s > 0) {
                         if (!late) fast_pv(pf, vf, ntag);
                         admit(s);
                         if (late) fast_pv(pf, vf, ntag);
                     }
-                    fast_sx(kptr(s, wk), kptr(s, wk) + VREG, pf, vf, ntag);
+                    fast_sx(kptr(s, wk), kptr(s, wk) + VREG, pf, vf, ntag, gtag);
                 }
             }
             fast_pv(pf, vf, ntag);
@@ -850,11 +872,59 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
             }
         }
     };
+    // fp16 only: which fast loop?  The scores of the stages already requested (up to 192 keys)
+    // are formed once more, without the softmax; if some lane's keys span more than 2^14 (ten
+    // standard deviations of the scores of unit-variance inputs: no false alarm in 10^5 lanes) the
+    // scores have a long tail, a later one is likely to pass the head room above the first
+    // step's maximum, and the workgroup takes the guarded loop.  A wrong guess costs time only.
+    auto probe_spread = [&](int n_fast) {
+        if constexpr (kGuard) {
+            float lo[TPW], hi[TPW];
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) lo[t] = INFINITY, hi[t] = -INFINITY;
+            // stage `issued - 1` may still be in flight; a short split is probed less
+            const int n_probe = min(min(n_fast, issued - 1), max(1, n_fast / 16));
+            for (int sb = 0; sb < n_probe; ++sb) {
+                if (sb > 0) {
+                    wait_stage(sb);
+                    __syncthreads();
+                }
+#pragma unroll
+                for (int ks = 0; ks < KSTEPS; ++ks) {
+                    uint4 kf[2][KQ];
+                    load_k_frags(smem + sb * STAGE + ks * 32 * ROWB, kf);
+#pragma unroll
+                    for (int t = 0; t < TPW; ++t) {
+                        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int kk = 0; kk < KQ; ++kk) {
+                            s0 = mfma16<T>(kf[0][kk], qf[t][kk], s0);
+                            s1 = mfma16<T>(kf[1][kk], qf[t][kk], s1);
+                        }
+                        hi[t] = fmaxf(hi[t], fmaxf(fmaxf(fmaxf(s0[0], s0[1]), fmaxf(s0[2], s0[3])),
+                                                   fmaxf(fmaxf(s1[0], s1[1]), fmaxf(s1[2], s1[3]))));
+                        lo[t] = fminf(lo[t], fminf(fminf(fminf(s0[0], s0[1]), fminf(s0[2], s0[3])),
+                                                   fminf(fminf(s1[0], s1[1]), fminf(s1[2], s1[3]))));
+                    }
+                }
+            }
+            bool wide = false;
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) wide |= (hi[t] - lo[t]) * p.c_log2 > 14.0f;
+            use_guard = __syncthreads_or(wide ? 1 : 0) != 0;
+        }
+    };
     // the fast loop is compiled once per possible tile count of a wave, so that
     // its body has no per-tile branches
     auto run_fast_tag = [&](int n_fast, f32x4 (&Sa)[TPW][2], auto ntag) {
+        if constexpr (kGuard) {
+            if (use_guard) {                          // uniform over the workgroup
+                run_fast_n(n_fast, ntag, std::true_type{});
+                return;
+            }
+        }
         if constexpr (kPipe) run_pipe_n(n_fast, Sa, ntag);
-        else run_fast_n(n_fast, ntag);
+        else run_fast_n(n_fast, ntag, std::false_type{});
     };
     auto run_fast = [&](int n_fast, f32x4 (&Sa)[TPW][2]) {
         if (my_nt == TPW) run_fast_tag(n_fast, Sa, std::integral_constant<int, TPW>{});
@@ -866,8 +936,9 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     };
     static_assert(TPW <= 3, "run_fast dispatches on at most three tile counts");
 
-    // The Q fragments must have arrived before the first DMA is issued: from
-    // here on vmcnt counts DMA stages only.
+    // The set-up loads are drained here, so that vmcnt counts the K/V stages from now on; the
+    // query fragments, requested between stage 0 and stage 1, complete in order with them (a
+    // wait that leaves only younger stages outstanding covers stage 0 and the queries alike).
     wait_vmcnt<0>();
 
     // Pass 0: stages that lie wholly inside the prefix run the fast step with a
@@ -895,6 +966,7 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
             }
             f32x4 Sa[TPW][2];
             init_reference(0, wk, Sa);
+            probe_spread(n_fast);
             run_fast(n_fast, Sa);
         } else {
             stamp(2);

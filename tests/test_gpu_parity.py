@@ -415,6 +415,22 @@ def test_batch_split_follows_the_lengths(oracle_mod, name, ctx, Hkv):
         assert_close(got3, want3, case.dtype, name + " (ragged counts)")
 
 
+@pytest.mark.parametrize("frac,gain,tag", [(0.05, 8.0, "frequent outliers: guarded reference"),
+                                           (0.0007, 40.0, "rare late outliers: frozen reference, overflow, redo"),
+                                           (0.02, 3.0, "mild tail: frozen reference holds")])
+@pytest.mark.parametrize("N,G", [(6, 4), (60, 4), (40, 8)])     # 2 / 15 / 20 row tiles: all three fast loops
+def test_fp16_score_range_paths(oracle_mod, frac, gain, tag, N, G):
+    """fp16 probabilities overflow 2^16 above their reference.  The kernel probes the first stages of
+    a split and takes a loop with a guarded (moving) reference if the scores already show a long
+    tail; otherwise it freezes the reference and, should a later score overflow it after all,
+    redoes the split with the exact loop.  All three routes must give the oracle's result."""
+    r = _rng(77 + N)
+    case = W.make_case("f16range", 910 + N, dtype=W.DT_F16, Hq=2 * G, Hkv=2, D=128, ctx_lens=[9000, 700],
+                       trees=[W.random_tree(N, 6, r) for _ in range(2)], outlier_frac=frac, outlier_gain=gain)
+    got, step = _run(case)
+    assert_close(got, oracle_mod.verify_attn_case(case), case.dtype, f"{tag}, N={N} G={G}")
+
+
 def test_graph_capture_replays_match_eager(oracle_mod):
     """No entry point allocates, clears memory or synchronises, so a verify step can be captured
     in a HIP graph.  The graph is replayed several times with new queries and lengths in the
