@@ -100,7 +100,14 @@ __global__ void __launch_bounds__(kProjWaves * 64) drafter_proj_kernel(const uin
 #pragma unroll
         for (int nb = 0; nb < kProjTiles; ++nb) acc[pt][nb] = d_f32x4{0.f, 0.f, 0.f, 0.f};
 
-    for (int ks0 = wave * kProjUnroll; ks0 < k_steps; ks0 += kProjWaves * kProjUnroll) {
+    // With more than 16 state rows the h fragments weigh as much as the weights in the L1/L2
+    // traffic, and every workgroup of the chip asks for the same lines of h at the same time if
+    // all sweep k in the same order: each starts at a round of its own instead.
+    const int rounds = (k_steps + kProjWaves * kProjUnroll - 1) / (kProjWaves * kProjUnroll);
+    const int first = PT > 1 ? (int)((blockIdx.x * 7u) % (unsigned)rounds) : 0;
+    for (int it = 0; it < rounds; ++it) {
+        const int rr = it + first < rounds ? it + first : it + first - rounds;
+        const int ks0 = (rr * kProjWaves + wave) * kProjUnroll;
         d_i32x4 b[kProjUnroll][kProjTiles], a[kProjUnroll][PT];
 #pragma unroll
         for (int u = 0; u < kProjUnroll; ++u) {
