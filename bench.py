@@ -13,7 +13,8 @@ step scans 32-80 layers' caches, so the cache is always cold, and the chip's
 Prints ONE JSON line.  `value` is algorithmic KV bytes per second
 (sum_b (L_b + N) * Hkv * D * 2 tensors * 2 bytes, divided by the time of the
 whole step); `ms_per_step` is the verify-step time.  `roofline` prices the
-split-KV kernel alone against the 8 TB/s HBM peak; `cpu_baseline` times the CPU
+split-KV kernel alone (HIP events around it in every fourth timed step) against the
+8 TB/s HBM peak; `cpu_baseline` times the CPU
 oracle on a sample of output rows on this machine's host cores.
 """
 from __future__ import annotations
@@ -96,6 +97,33 @@ class Rotating:
             self.run()
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
+
+    def time_steps_with_kernel(self, steps, warmup):
+        """The timed region with the split-KV kernel of every fourth timed step bracketed by HIP
+        events on the launch stream (such a step is enqueued as its two phases: the same two
+        kernels; the event records cost a short step a few microseconds, hence not every step).
+        Returns (seconds per step, average and median seconds of the split-KV kernel)."""
+        torch = self.torch
+        every = 4
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range((steps + every - 1) // every)]
+        for _ in range(warmup):
+            self.run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            if i % every == 0:
+                a, b = ev[i // every]
+                a.record()
+                self.run(phases=1)
+                b.record()
+                self.run(phases=2)
+            else:
+                self.run()
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / steps
+        ms = sorted(a.elapsed_time(b) for a, b in ev)
+        return sec, sum(ms) / len(ms) * 1e-3, ms[len(ms) // 2] * 1e-3
 
     def time_split_kernel(self, steps):
         """Average duration of the split-KV kernel alone, from events recorded
@@ -351,7 +379,10 @@ def bench_config(idx, args, want_detail):
     from paper_2510_07535_amd import workloads as W
     case = W.make_config(idx, dtype={"bf16": W.DT_BF16, "f16": W.DT_F16}[args.dtype])
     rot = Rotating(case, split_tokens=args.split_tokens)
-    sec = rot.time_steps(args.steps, args.warmup)
+    if want_detail:
+        sec, kavg, kmed = rot.time_steps_with_kernel(args.steps, args.warmup)
+    else:
+        sec = rot.time_steps(args.steps, args.warmup)
     res = {
         "workload": W.CONFIG_NAMES[idx], "config_index": idx,
         "us_per_step": sec * 1e6, "GBps": rot.kv_bytes / sec / 1e9,
@@ -359,7 +390,6 @@ def bench_config(idx, args, want_detail):
         "kv_bytes": rot.kv_bytes, "plan": rot.step.plan.as_dict(), "kv_copies_rotated": len(rot.pools),
     }
     if want_detail:
-        kavg, kmed = rot.time_split_kernel(min(args.steps, 100))
         res["split_kernel_avg_s"] = kavg
         res["split_kernel_median_s"] = kmed
     assert rot.step.dev_status() == 0
