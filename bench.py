@@ -320,18 +320,21 @@ def bench_drafter(steps=60, with_cpu=True):
         for _ in range(5):
             run()
         torch.cuda.synchronize()
+        every = 4                                        # the projection of every fourth timed step between events
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range((steps + every - 1) // every)]
         t0 = time.perf_counter()
-        for _ in range(steps):
-            run()
+        for i in range(steps):
+            if i % every == 0:
+                a, b = ev[i // every]
+                a.record()
+                run(phases=1)
+                b.record()
+                run(phases=2)
+            else:
+                run()
         torch.cuda.synchronize()
         sec = (time.perf_counter() - t0) / steps
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
-        for a, b in ev:
-            a.record()
-            run(phases=1)
-            b.record()
-            run(phases=2)
-        torch.cuda.synchronize()
         ksec = sum(a.elapsed_time(b) for a, b in ev) / len(ev) * 1e-3
         assert step.dev_status() == 0
         res = {"workload": name, "d_in": d_in, "d": d, "n_states": P, "n_rows": M, "dtype": "bf16",
