@@ -75,17 +75,9 @@ def chain_tree(n: int) -> np.ndarray:
     return np.arange(-1, n - 1, dtype=np.int32)
 
 
-def node_depths(parent: Sequence[int]) -> np.ndarray:
-    """Depth with the root counted as 1 (a chain of n nodes has depth n)."""
-    d = np.zeros(len(parent), dtype=np.int32)
-    for i, p in enumerate(parent):
-        d[i] = 1 if p < 0 else d[p] + 1
-    return d
-
-
-def random_tree(n: int, max_depth: Optional[int], rng: np.random.Generator) -> np.ndarray:
-    """Node 0 is the root; every later node draws its parent uniformly from
-    the earlier nodes whose depth is below ``max_depth`` (root depth = 1)."""
+def _grow_tree(n: int, max_depth: Optional[int], rng: np.random.Generator):
+    """(parent, level) of a random tree; ``level`` is the bookkeeping the draw itself
+    needs (which earlier nodes may still take a child): 1 for the root, parent's + 1 below."""
     if max_depth is not None and max_depth < 2 and n > 1:
         raise ValueError("a tree of several nodes under one root needs max_depth >= 2")
     parent = np.full(n, -1, dtype=np.int32)
@@ -99,25 +91,23 @@ def random_tree(n: int, max_depth: Optional[int], rng: np.random.Generator) -> n
         p = int(cand[rng.integers(0, len(cand))])
         parent[i] = p
         depth[i] = depth[p] + 1
-    return parent
+    return parent, depth
+
+
+def random_tree(n: int, max_depth: Optional[int], rng: np.random.Generator) -> np.ndarray:
+    """Node 0 is the root; every later node draws its parent uniformly from
+    the earlier nodes whose depth is below ``max_depth`` (root depth = 1)."""
+    return _grow_tree(n, max_depth, rng)[0]
 
 
 def hybrid_tree(n_tree: int, n_chain: int, rng: np.random.Generator) -> np.ndarray:
     """A random tree with a chain hung off its deepest leaf (lowest index on
     ties); the chain nodes take the indices after the tree's."""
-    t = random_tree(n_tree, None, rng)
-    d = node_depths(t)
+    t, d = _grow_tree(n_tree, None, rng)
     leaf = int(np.argmax(d))  # argmax returns the first maximal entry
     chain = np.arange(n_tree - 1, n_tree + n_chain - 1, dtype=np.int32)
     chain[0] = leaf
     return np.concatenate([t, chain]).astype(np.int32)
-
-
-def spec_tree(parent: Sequence[int]) -> np.ndarray:
-    """Sec. 3.2.2 decode stage: one extra leaf per node, following that node's
-    root path; leaf k (index n+k) hangs off node k."""
-    n = len(parent)
-    return np.concatenate([np.asarray(parent, np.int32), np.arange(n, dtype=np.int32)])
 
 
 # ----------------------------------------------------------------------------

@@ -8,6 +8,7 @@ from paper_2510_07535_amd import binding as B
 from paper_2510_07535_amd import workloads as W
 from paper_2510_07535_amd.runner import VerifyStep, _to_dev
 from util import assert_close, sample_rows
+from tree_helpers import spec_tree
 
 pytestmark = pytest.mark.gpu
 
@@ -63,7 +64,7 @@ def _small_cases():
         mk("bf16_forest", 113, dtype=W.DT_BF16, Hq=4, Hkv=1, D=128, ctx_lens=[300],
            trees=[np.array([-1, -1, 0, 1, 1, -1, 5, 2], np.int32)]),
         # fp16 storage (the paper's inference type)
-        mk("f16_tree30", 114, dtype=W.DT_F16, Hq=16, Hkv=4, D=128, ctx_lens=[1100], trees=[W.spec_tree(W.random_tree(15, 4, r))]),
+        mk("f16_tree30", 114, dtype=W.DT_F16, Hq=16, Hkv=4, D=128, ctx_lens=[1100], trees=[spec_tree(W.random_tree(15, 4, r))]),
         # fp16 (the paper's dtype) through the fast loop: long enough for many fast stages; with
         # outlier keys the fp16 P overflows its stale reference and the split is redone
         mk("f16_tree60_L5000", 117, dtype=W.DT_F16, Hq=8, Hkv=2, D=128, ctx_lens=[5000], trees=[W.random_tree(60, 6, r)]),
@@ -219,7 +220,7 @@ def test_quad_max_lane_semantics():
 def test_tree_mask_bit_exact(oracle_mod):
     r = _rng(10)
     trees64 = [W.random_tree(64, md, r) for md in (None, 2, 8)] + [W.chain_tree(64), np.full(64, -1, np.int32)]
-    trees6 = [W.spec_tree([-1, 0, 0]), W.chain_tree(6)]
+    trees6 = [spec_tree([-1, 0, 0]), W.chain_tree(6)]
     for trees in (trees64, trees6, [W.chain_tree(1)]):
         par = np.stack(trees).astype(np.int32)
         Bn, N = par.shape

@@ -13,6 +13,7 @@ import pytest
 import torch
 
 from paper_2510_07535_amd import workloads as W
+from tree_helpers import node_depths, spec_tree
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -80,7 +81,7 @@ def small_cases():
     cs.append(W.make_case("bf_d", 14, dtype=W.DT_BF16, Hq=8, Hkv=1, D=64, ctx_lens=[50],
                           trees=[np.array([-1, -1, 0, 1, 1, -1], np.int32)], paged=False))
     cs.append(W.make_case("bf_e", 15, dtype=W.DT_F32, Hq=2, Hkv=1, D=4, ctx_lens=[1],
-                          trees=[W.spec_tree([-1, 0, 0])], scale=0.37))
+                          trees=[spec_tree([-1, 0, 0])], scale=0.37))
     return cs
 
 
@@ -146,7 +147,7 @@ def test_zero_query_gives_mean_of_visible_values(oracle_mod):
         while j != -1:
             path.append(j)
             j = int(tree[j])
-        assert len(path) == W.node_depths(tree)[i]
+        assert len(path) == node_depths(tree)[i]
         idx = list(range(23)) + [23 + j for j in path]
         for h in range(case.Hq):
             np.testing.assert_allclose(got[0, i, h], V[idx, h // 2].mean(axis=0), atol=1e-13)
@@ -294,7 +295,7 @@ def _golden():
 
 def test_tree_mask_matches_paper_example(oracle_mod):
     parent, masks, depth = _golden()
-    assert np.array_equal(parent, W.spec_tree([-1, 0, 0]))
+    assert np.array_equal(parent, spec_tree([-1, 0, 0]))
     anc, dep = oracle_mod.tree_mask(parent)
     assert np.array_equal(anc, masks)
     assert np.array_equal(dep, depth)
@@ -348,9 +349,9 @@ def test_generators_follow_the_recipe():
     rng = np.random.Generator(np.random.Philox(key=7))
     t = W.random_tree(60, 6, rng)
     assert t[0] == -1 and all(0 <= t[i] < i for i in range(1, 60))
-    assert W.node_depths(t).max() <= 6
+    assert node_depths(t).max() <= 6
     h = W.hybrid_tree(32, 8, rng)
-    d = W.node_depths(h)
+    d = node_depths(h)
     assert len(h) == 40 and all(h[k] == k - 1 for k in range(33, 40))
     assert d[h[32]] == d[:32].max() and h[32] == int(np.argmax(d[:32]))
     assert np.array_equal(W.chain_tree(4), [-1, 0, 1, 2])

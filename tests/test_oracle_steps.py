@@ -10,6 +10,7 @@ import pytest
 import oracle
 from oracle import steps as S
 from paper_2510_07535_amd import workloads as W
+from tree_helpers import node_depths
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "spec_tree_example.txt")
 
@@ -126,7 +127,7 @@ def test_accept_properties_random(seed):
     tgt = rng.integers(0, 4, size=(B, N))
     root = rng.integers(0, 4, size=B)
     acc, na, bonus, last = S.accept_greedy(tok, parent, root, tgt, N)
-    depth = np.stack([W.node_depths(p) for p in parent])
+    depth = np.stack([node_depths(p) for p in parent])
     for b in range(B):
         agrees = np.zeros(N, bool)                                     # forward sweep, independent of the enumeration
         for i in range(N):
