@@ -11,8 +11,8 @@
  *     parallel pass whose cost, in the memory-bound regime, is the scan of the
  *     cached context.
  *   - Sec. 3.2.2 "Decode Stage" and Algorithm 1 (Prepare / OurTreeVerify): a
- *     token placed after a tree path sees exactly that path; realised by
- *     "manipulating the attention mask".  The example there fixes the rule:
+ *     token placed after a tree path sees exactly that path; the paper gets
+ *     there by adjusting the attention mask.  The example there fixes the rule:
  *     ancestor-or-self visibility among the drafts, full visibility of the
  *     prefix.
  *   - Sec. 3.2.3 / Algorithm 1 (NonTreeVerify): sequence verification is the
@@ -185,8 +185,8 @@ owl_status owl_verify_attn_ragged(const owl_verify_desc *desc, const void *q, co
                                   size_t workspace_bytes, uint32_t *dev_status, void *stream);
 
 /*
- * The attention mask of a drafted tree in packed form (Sec. 3.2.2: "manipulating
- * the position ids and attention mask"; Algorithm 1, Prepare): for every
+ * The attention mask of a drafted tree in packed form (Sec. 3.2.2, where the
+ * mask and the position ids are adjusted to the tree; Algorithm 1, Prepare): for every
  * sequence b and node i,
  *     anc_mask[b][i]  bit j set  <=>  node j is on the path from i to its root,
  *                                     i itself included
@@ -251,6 +251,10 @@ owl_status owl_accept_greedy(const int32_t *tokens, const int32_t *tree_parent, 
  * new_ctx_lens[b] = ctx_lens[b] + n_accept[b]; it may be NULL but must not be
  * ctx_lens itself.  accepted[b][0..n_accept) must be strictly increasing and in
  * [0, N) (a root path is), else nothing moves for b and OWL_DEV_BAD_ACCEPT is set.
+ * Likewise, if a page-table entry under any source or destination row of b is
+ * outside the pool (or the position lies beyond the table), nothing moves for
+ * b, new_ctx_lens[b] = ctx_lens[b] and OWL_DEV_BAD_PAGE is set: a call that
+ * writes never substitutes another page for a bad one.
  * The caches are written; everything else is read only.
  */
 owl_status owl_commit_kv(const owl_verify_desc *desc, void *k_cache, void *v_cache, const int32_t *page_table,

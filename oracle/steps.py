@@ -5,8 +5,8 @@ numpy, written from the paper's description of the decode step, sharing
 nothing with the HIP path.
 
 * ``prepare_spec_tree``  -- Sec. 3.2.2 "Decode Stage" / Algorithm 1 ``Prepare``:
-  one extra token per tree node, placed after that node's root path, by
-  "manipulating the position ids and attention mask".
+  one extra token per tree node, placed after that node's root path; the mask
+  and the position ids are what place it there.
 * ``accept_greedy``      -- Sec. 1 / Sec. 2: the target model verifies the drafted
   tokens in one pass and keeps the longest drafted path that agrees with its own
   (greedy) choices, which leaves its output unchanged.

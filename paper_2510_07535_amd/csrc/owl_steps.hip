@@ -121,6 +121,11 @@ hipError_t launch_accept(const int32_t *tokens, const int32_t *parent, const int
 // first, the workgroup meets at a barrier, and only then anything is stored.
 // accepted[] must be strictly increasing (a root path in a tree whose parents
 // precede their children is); anything else is flagged and nothing is moved.
+// The same holds for pages: every source and destination page of the sequence
+// is looked up before anything is loaded, and one entry outside the pool (or a
+// position beyond the table) means OWL_DEV_BAD_PAGE, no row of that sequence
+// moves, and its new length equals the old one.  A kernel that writes must not
+// replace a bad page by some other page.
 // ---------------------------------------------------------------------------
 constexpr int kCommitThreads = 256;
 constexpr int kCommitMaxPieces = 8;                         // 64 rows x 32 pieces / 256 threads
@@ -132,13 +137,14 @@ __global__ void __launch_bounds__(kCommitThreads) commit_kernel(
     int64_t stride_token, int32_t *new_ctx_lens, uint32_t *status)
 {
     __shared__ int32_t s_src[64];
-    __shared__ int s_bad;
+    __shared__ int64_t s_src_page[64], s_dst_page[64];
+    __shared__ int s_bad, s_bad_page;
     const int g = blockIdx.x, b = blockIdx.y;
     unsigned char *cache = blockIdx.z ? v_cache : k_cache;
     const int tid = threadIdx.x;
     const int L = load_ctx_len(ctx_lens, b, max_ctx_len, status);
     int na = n_accept[b];
-    if (tid == 0) s_bad = 0;
+    if (tid == 0) s_bad = s_bad_page = 0;
     __syncthreads();
     if (na < 0 || na > N) {
         if (tid == 0) flag_status(status, OWL_DEV_BAD_ACCEPT);
@@ -149,10 +155,23 @@ __global__ void __launch_bounds__(kCommitThreads) commit_kernel(
         const int prev = tid > 0 ? accepted[(int64_t)b * N + tid - 1] : -1;
         if (a < 0 || a >= N || a <= prev) s_bad = 1;
         s_src[tid] = a;
+        // physical pages of the row's source and destination, unchecked ids; -1 = not in the table
+        auto page_of = [&](int pos) -> int64_t {
+            const int lp = pos / kPage;
+            if (!page_table) return lp;
+            return lp < max_pages ? (int64_t)page_table[(int64_t)b * max_pages + lp] : -1;
+        };
+        const int64_t sp = (a >= 0 && a < N) ? page_of(L + a) : 0, dp = page_of(L + tid);
+        if (sp < 0 || sp >= n_pool_pages || dp < 0 || dp >= n_pool_pages) s_bad_page = 1;
+        s_src_page[tid] = sp;
+        s_dst_page[tid] = dp;
     }
     __syncthreads();
     if (s_bad) {                                            // uniform over the workgroup
         if (tid == 0) flag_status(status, OWL_DEV_BAD_ACCEPT);
+        na = 0;
+    } else if (s_bad_page) {
+        if (tid == 0) flag_status(status, OWL_DEV_BAD_PAGE);
         na = 0;
     }
     if (g == 0 && blockIdx.z == 0 && tid == 0 && new_ctx_lens) new_ctx_lens[b] = L + na;
@@ -166,8 +185,7 @@ __global__ void __launch_bounds__(kCommitThreads) commit_kernel(
         if (id < total) {
             const int i = id / ppr, piece = id % ppr;
             const int pos = L + s_src[i];
-            const int64_t pg = load_page(page_table, b, max_pages, n_pool_pages, pos / kPage, status);
-            const int64_t off = (pg * stride_page + g * stride_head + (pos % kPage) * stride_token) * es;
+            const int64_t off = (s_src_page[i] * stride_page + g * stride_head + (pos % kPage) * stride_token) * es;
             held[r] = *reinterpret_cast<const uint4 *>(cache + off + piece * 16);
         }
     }
@@ -179,8 +197,7 @@ __global__ void __launch_bounds__(kCommitThreads) commit_kernel(
             const int i = id / ppr, piece = id % ppr;
             if (s_src[i] != i) {                            // a row already in place is left alone
                 const int pos = L + i;
-                const int64_t pg = load_page(page_table, b, max_pages, n_pool_pages, pos / kPage, status);
-                const int64_t off = (pg * stride_page + g * stride_head + (pos % kPage) * stride_token) * es;
+                const int64_t off = (s_dst_page[i] * stride_page + g * stride_head + (pos % kPage) * stride_token) * es;
                 *reinterpret_cast<uint4 *>(cache + off + piece * 16) = held[r];
             }
         }

@@ -218,3 +218,31 @@ def test_commit_flags_bad_lists_and_moves_nothing():
                           case.stride_head, case.stride_token, case.Hkv, case.D)
     got = step.k.cpu().numpy().view(case.k_pool.dtype).reshape(case.k_pool.shape)
     assert np.array_equal(got, want)
+
+
+def test_commit_with_a_bad_page_moves_nothing_for_that_sequence():
+    """A page-table entry outside the pool under a source or a destination row: the sequence is
+    flagged and left alone (pools byte-identical, length unchanged); the other sequences commit."""
+    case = _commit_case(W.DT_BF16, 128, True, True, 61)
+    acc, na = _random_paths(case, _rng(62))
+    assert na[0] > 0 and na[1] > 0
+    for which in ("destination", "source"):
+        table = case.page_table.copy()
+        L0 = int(case.ctx_lens[0])
+        pos = L0 if which == "destination" else L0 + int(acc[0, na[0] - 1])
+        table[0, pos // 16] = -1
+        step = VerifyStep(case)
+        step.page_table = _i32(table)
+        new_ctx = torch.zeros(case.B, dtype=torch.int32, device=DEV)
+        B.owl_commit_kv(step.desc, step.k, step.v, step.page_table, step.ctx_lens, _i32(acc), _i32(na), new_ctx,
+                        step.status)
+        torch.cuda.synchronize()
+        assert step.dev_status() & B.OWL_DEV_BAD_PAGE, which
+        na_eff = na.copy()
+        na_eff[0] = 0                                                  # what the flagged sequence is reduced to
+        for name, pool, dev in (("k", case.k_pool, step.k), ("v", case.v_pool, step.v)):
+            want, want_ctx = S.commit_kv(pool, case.page_table, case.ctx_lens, acc, na_eff, case.stride_page,
+                                         case.stride_head, case.stride_token, case.Hkv, case.D)
+            got = dev.cpu().numpy().view(pool.dtype).reshape(pool.shape)
+            assert np.array_equal(got.view(np.uint8), want.view(np.uint8)), (which, name)
+            assert np.array_equal(new_ctx.cpu().numpy(), want_ctx), which
