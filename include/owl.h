@@ -152,6 +152,42 @@ owl_status owl_verify_attn(const owl_verify_desc *desc, const void *q, const voi
                            void *stream);
 
 /*
+ * One-time set-up for `desc` on the current device, host only: the kernel that
+ * serves `desc` needs more LDS than the default and is told so once per device
+ * (hipFuncSetAttribute), and the device address of the library's own scratch
+ * memory (owl_verify_attn_noalloc) is looked up.  Every entry point does this
+ * by itself on first use; a caller who wants the FIRST call for a shape to be
+ * legal inside a stream capture (where such calls are not allowed) calls this
+ * beforehand, outside the capture.  Launches nothing.
+ */
+owl_status owl_verify_attn_init(const owl_verify_desc *desc);
+
+/*
+ * owl_verify_attn for callers that cannot allocate device memory and have no
+ * workspace to hand over: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * result as owl_verify_attn, minus the workspace: the split partials go to a
+ * fixed buffer of OWL_NOALLOC_SCRATCH_BYTES inside the library's own device
+ * image (one per GPU that loads the library, held until the process ends).
+ *   - A `desc` whose owl_verify_attn_workspace_size exceeds
+ *     OWL_NOALLOC_SCRATCH_BYTES is refused with OWL_ERR_WORKSPACE before
+ *     anything is launched (the single-sequence shapes up to 128K context with
+ *     320 rows per KV head fit; a large batch does not).
+ *   - Calls no hipMalloc / hipFree or any other allocating routine.  The first
+ *     call on a device looks up the buffer's address (owl_verify_attn_init
+ *     does the same ahead of time).
+ *   - All calls on one GPU share the one buffer: calls that may overlap in
+ *     time (different streams, different threads) race and give garbage; order
+ *     them on one stream.  The buffer keeps the previous call's contents;
+ *     nothing in it needs to start at zero.
+ */
+#define OWL_NOALLOC_SCRATCH_BYTES (48u << 20)
+owl_status owl_verify_attn_noalloc(const owl_verify_desc *desc, const void *q, const void *k_cache,
+                                   const void *v_cache, const int32_t *page_table,
+                                   const int32_t *ctx_lens, const int32_t *tree_parent, float *out,
+                                   uint32_t *dev_status, void *stream);
+
+/*
  * The same step, one phase at a time, for measurement: `phases` is a bit set of
  * OWL_PHASE_SPLIT (the split-KV pass that scans the cache and leaves partials
  * in the workspace) and OWL_PHASE_COMBINE (the log-sum-exp merge that turns

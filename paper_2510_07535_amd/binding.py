@@ -31,8 +31,10 @@ EXPORTS = (
     "owl_prepare_spec_tree", "owl_accept_greedy", "owl_commit_kv", "owl_verify_attn_ragged",
     "owl_drafter_cell", "owl_drafter_cell_phases", "owl_drafter_cell_workspace_size", "owl_drafter_alpha",
     "owl_drafter_tiled_weight_bytes", "owl_drafter_tile_weights",
+    "owl_verify_attn_init", "owl_verify_attn_noalloc",
     "owl_status_str", "owl_version",
 )
+OWL_NOALLOC_SCRATCH_BYTES = 48 << 20
 
 
 class VerifyDesc(ctypes.Structure):
@@ -100,6 +102,10 @@ def lib() -> ctypes.CDLL:
         l.owl_verify_attn.restype = ctypes.c_int
         l.owl_verify_attn.argtypes = [ctypes.POINTER(VerifyDesc), vp, vp, vp, vp, vp, vp, vp,
                                       vp, ctypes.c_size_t, vp, vp]
+        l.owl_verify_attn_init.restype = ctypes.c_int
+        l.owl_verify_attn_init.argtypes = [ctypes.POINTER(VerifyDesc)]
+        l.owl_verify_attn_noalloc.restype = ctypes.c_int
+        l.owl_verify_attn_noalloc.argtypes = [ctypes.POINTER(VerifyDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp]
         l.owl_verify_attn_ragged.restype = ctypes.c_int
         l.owl_verify_attn_ragged.argtypes = [ctypes.POINTER(VerifyDesc), vp, vp, vp, vp, vp, vp, vp, vp,
                                              vp, ctypes.c_size_t, vp, vp]
@@ -199,6 +205,19 @@ def owl_verify_attn(desc: VerifyDesc, q, k_cache, v_cache, page_table, ctx_lens,
                                _ptr(workspace), ws_bytes, _ptr(dev_status),
                                _stream() if stream is None else stream)
     _check(rc, "owl_verify_attn")
+
+
+def owl_verify_attn_init(desc: VerifyDesc) -> None:
+    _check(lib().owl_verify_attn_init(ctypes.byref(desc)), "owl_verify_attn_init")
+
+
+def owl_verify_attn_noalloc(desc: VerifyDesc, q, k_cache, v_cache, page_table, ctx_lens, tree_parent, out,
+                            dev_status=None, stream: Optional[int] = None) -> None:
+    """owl_verify_attn without a workspace argument (the library's own fixed scratch buffer)."""
+    rc = lib().owl_verify_attn_noalloc(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                       _ptr(page_table), _ptr(ctx_lens), _ptr(tree_parent), _ptr(out),
+                                       _ptr(dev_status), _stream() if stream is None else stream)
+    _check(rc, "owl_verify_attn_noalloc")
 
 
 PHASE_SPLIT, PHASE_COMBINE, PHASE_ALL = 1, 2, 3

@@ -178,6 +178,29 @@ owl_status ensure_lds_attr(const Variant *v)
 
 long long *g_timeline = nullptr;   // set by owl_debug_set_timeline
 
+// Device memory of owl_verify_attn_noalloc: the split partials live here instead of in a
+// caller's workspace.  One copy per GPU that loads the library, held until the process ends.
+// In host code the array's name is only a handle: its device address comes from
+// hipGetSymbolAddress, once per device (scratch_address), and only that address is ever
+// handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[OWL_NOALLOC_SCRATCH_BYTES];
+
+owl_status scratch_address(void **out)
+{
+    static std::mutex mu;
+    static void *addr[16] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return OWL_ERR_HIP;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return OWL_ERR_HIP;
+        addr[dev] = ptr;
+    }
+    *out = addr[dev];
+    return OWL_OK;
+}
+
 bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
 
 }  // namespace
@@ -295,6 +318,32 @@ static owl_status verify_impl(const owl_verify_desc *desc, const void *q, const 
     if (phases & OWL_PHASE_COMBINE)
         if (launch_combine(p, desc->head_dim, s) != hipSuccess) return OWL_ERR_HIP;
     return OWL_OK;
+}
+
+owl_status owl_verify_attn_init(const owl_verify_desc *desc)
+{
+    FullPlan fp;
+    owl_status st = make_plan(desc, &fp);
+    if (st != OWL_OK) return st;
+    st = ensure_lds_attr(fp.variant);
+    if (st != OWL_OK) return st;
+    void *ptr = nullptr;
+    return scratch_address(&ptr);
+}
+
+owl_status owl_verify_attn_noalloc(const owl_verify_desc *desc, const void *q, const void *k_cache,
+                                   const void *v_cache, const int32_t *page_table, const int32_t *ctx_lens,
+                                   const int32_t *tree_parent, float *out, uint32_t *dev_status, void *stream)
+{
+    FullPlan fp;
+    owl_status st = make_plan(desc, &fp);
+    if (st != OWL_OK) return st;
+    if (fp.pub.workspace_bytes > (size_t)OWL_NOALLOC_SCRATCH_BYTES) return OWL_ERR_WORKSPACE;
+    void *ptr = nullptr;
+    st = scratch_address(&ptr);
+    if (st != OWL_OK) return st;
+    return verify_impl(desc, q, k_cache, v_cache, page_table, ctx_lens, tree_parent, nullptr, out, ptr,
+                       (size_t)OWL_NOALLOC_SCRATCH_BYTES, dev_status, stream, OWL_PHASE_ALL);
 }
 
 owl_status owl_build_tree_mask(const int32_t *tree_parent, int32_t batch, int32_t n_draft,
