@@ -12,10 +12,16 @@ step scans 32-80 layers' caches, so the cache is always cold, and the chip's
 
 Prints ONE JSON line.  `value` is algorithmic KV bytes per second
 (sum_b (L_b + N) * Hkv * D * 2 tensors * 2 bytes, divided by the time of the
-whole step); `ms_per_step` is the verify-step time.  `roofline` prices the
-split-KV kernel alone (HIP events around it in every fourth timed step) against the
-8 TB/s HBM peak; `cpu_baseline` times the CPU
-oracle on a sample of output rows on this machine's host cores.
+whole step); `ms_per_step` is the verify-step time: wall clock over exactly
+--steps steps between two synchronisations.  `roofline` prices the split-KV
+kernel alone from HIP events around its launches (every fourth step of the
+timed region, plus a sampling pass after it so that there are at least 32
+samples whatever --steps is) against whichever of the two roofs bounds the
+shape: 8 TB/s of HBM over the algorithmic K/V bytes or 2.5 PFLOP/s of dense
+bf16 MFMA over the algorithmic flop; both sides are printed.  `step_us` holds
+percentiles of single steps (an event after every step of a separate pass).
+`others` repeats this for the other bf16 workloads.  `cpu_baseline` times the
+CPU oracle on a sample of output rows on this machine's host cores.
 """
 from __future__ import annotations
 
@@ -30,7 +36,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = 2500.0
 MIN_ROTATION_BYTES = 2 << 30
+MIN_KERNEL_SAMPLES = 32
+STEP_SAMPLES = 96
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
 
 
@@ -51,7 +60,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=3,
                     help="0-based index into the benchmark configurations (default 3: 128K-context hybrid verify)")
-    ap.add_argument("--all", action="store_true", help="also time the other bf16 configurations (reported under 'others')")
+    ap.add_argument("--all", action="store_true",
+                    help="also time the steps around the attention and the drafter cell ('step_kernels', 'drafter_cell')")
+    ap.add_argument("--no-others", action="store_true", help="time only the --config workload (no 'others')")
     ap.add_argument("--split-tokens", type=int, default=0, help="override the library's split size (tuning)")
     ap.add_argument("--dtype", choices=("bf16", "f16"), default="bf16",
                     help="storage type of q/K/V (the configurations list bf16; f16 is the paper's type)")
@@ -99,14 +110,15 @@ class Rotating:
         return (time.perf_counter() - t0) / steps
 
     def time_steps_with_kernel(self, steps, warmup):
-        """The timed region with the split-KV kernel of every fourth timed step bracketed by HIP
-        events on the launch stream (such a step is enqueued as its two phases: the same two
-        kernels; the event records cost a short step a few microseconds, hence not every step).
-        Returns (seconds per step, average and median seconds of the split-KV kernel)."""
+        """The timed region (wall clock over exactly `steps` steps) with the split-KV kernel of every
+        fourth step bracketed by HIP events on the launch stream (such a step is enqueued as its two
+        phases: the same kernels), then two sampling passes outside it: more bracketed kernels until
+        there are MIN_KERNEL_SAMPLES, and STEP_SAMPLES steps with an event after each for the
+        distribution of single-step times.  Returns a dict of seconds."""
         torch = self.torch
         every = 4
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-              for _ in range((steps + every - 1) // every)]
+        new_pair = lambda: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+        ev = [new_pair() for _ in range((steps + every - 1) // every)]
         for _ in range(warmup):
             self.run()
         torch.cuda.synchronize()
@@ -122,26 +134,28 @@ class Rotating:
                 self.run()
         torch.cuda.synchronize()
         sec = (time.perf_counter() - t0) / steps
-        ms = sorted(a.elapsed_time(b) for a, b in ev)
-        return sec, sum(ms) / len(ms) * 1e-3, ms[len(ms) // 2] * 1e-3
-
-    def time_split_kernel(self, steps):
-        """Average duration of the split-KV kernel alone, from events recorded
-        on the launch stream right around each launch."""
-        torch = self.torch
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
-        for _ in range(3):
-            self.run()
-        torch.cuda.synchronize()
-        for a, b in ev:
+        n_timed = len(ev)
+        extra = [new_pair() for _ in range(max(0, MIN_KERNEL_SAMPLES - n_timed))]
+        for i, (a, b) in enumerate(extra):
+            for _ in range(every - 1):
+                self.run()
             a.record()
             self.run(phases=1)
             b.record()
             self.run(phases=2)
         torch.cuda.synchronize()
-        ms = sorted(a.elapsed_time(b) for a, b in ev)
-        return sum(ms) / len(ms) * 1e-3, ms[len(ms) // 2] * 1e-3
-
+        ks = sorted(a.elapsed_time(b) * 1e-3 for a, b in ev + extra)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(STEP_SAMPLES + 1)]
+        marks[0].record()
+        for m in marks[1:]:
+            self.run()
+            m.record()
+        torch.cuda.synchronize()
+        ss = sorted(marks[i].elapsed_time(marks[i + 1]) * 1e-3 for i in range(STEP_SAMPLES))
+        pct = lambda v, q: v[min(len(v) - 1, int(q * len(v)))]
+        return {"step": sec, "kernel_avg": sum(ks) / len(ks), "kernel_p10": pct(ks, 0.1), "kernel_p50": pct(ks, 0.5),
+                "kernel_p90": pct(ks, 0.9), "kernel_samples": len(ks), "kernel_samples_in_timed_region": n_timed,
+                "step_p10": pct(ss, 0.1), "step_p50": pct(ss, 0.5), "step_p90": pct(ss, 0.9), "step_samples": len(ss)}
 
 def stream_probe_gbs(nbytes=1 << 30):
     import torch
@@ -378,23 +392,47 @@ def bench_draft_sweep(ctx=65536, counts=(1, 4, 8, 16, 24, 32, 48, 60)):
     return out
 
 
-def bench_config(idx, args, want_detail):
+def roofline_of(case, t, workload):
+    """The split-KV kernel against both roofs; `bound` names the one with the longer floor."""
+    kbytes = case.kv_bytes()
+    rows_per_kv = (case.Hq // case.Hkv) * case.N
+    # QK^T and PV are 2*D flop each per (row, key)
+    flop = 4.0 * case.D * rows_per_kv * case.Hkv * float((case.ctx_lens.astype("int64") + case.N).sum())
+    ksec = t["kernel_avg"]
+    t_hbm, t_mfma = kbytes / (HBM_PEAK_GBS * 1e9), flop / (MFMA_PEAK_TFLOPS * 1e12)
+    hbm = {"achieved": kbytes / ksec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": t_hbm / ksec,
+           "floor_us": t_hbm * 1e6, "algorithmic_bytes_per_launch": kbytes}
+    mfma = {"achieved": flop / ksec / 1e12, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": t_mfma / ksec,
+            "floor_us": t_mfma * 1e6, "algorithmic_flop_per_launch": flop}
+    bound = "mfma" if t_mfma > t_hbm else "hbm"
+    top = dict(mfma if bound == "mfma" else hbm)
+    top.pop("floor_us")
+    r = {"bound": bound, **top,
+         "traffic": measured_traffic(workload), "traffic_source": "profiles/hbm_traffic.json (rocprofv3 FETCH_SIZE + "
+         "WRITE_SIZE of an earlier run of this workload, calibrated; not measured by this run)",
+         "kernel": "splitkv_kernel", "kernel_avg_us": ksec * 1e6, "kernel_p10_us": t["kernel_p10"] * 1e6,
+         "kernel_median_us": t["kernel_p50"] * 1e6, "kernel_p90_us": t["kernel_p90"] * 1e6,
+         "kernel_samples": t["kernel_samples"], "kernel_samples_in_timed_region": t["kernel_samples_in_timed_region"],
+         "t_hbm_us": t_hbm * 1e6, "t_mfma_us": t_mfma * 1e6, "hbm": hbm, "mfma": mfma}
+    return r
+
+
+def bench_config(idx, args):
     from paper_2510_07535_amd import workloads as W
     case = W.make_config(idx, dtype={"bf16": W.DT_BF16, "f16": W.DT_F16}[args.dtype])
     rot = Rotating(case, split_tokens=args.split_tokens)
-    if want_detail:
-        sec, kavg, kmed = rot.time_steps_with_kernel(args.steps, args.warmup)
-    else:
-        sec = rot.time_steps(args.steps, args.warmup)
+    t = rot.time_steps_with_kernel(args.steps, args.warmup)
+    sec = t["step"]
     res = {
         "workload": W.CONFIG_NAMES[idx], "config_index": idx,
         "us_per_step": sec * 1e6, "GBps": rot.kv_bytes / sec / 1e9,
         "frac_of_hbm_peak": rot.kv_bytes / sec / 1e9 / HBM_PEAK_GBS,
+        "step_us": {"p10": t["step_p10"] * 1e6, "p50": t["step_p50"] * 1e6, "p90": t["step_p90"] * 1e6,
+                    "samples": t["step_samples"], "how": "an event after every step of a separate pass"},
         "kv_bytes": rot.kv_bytes, "plan": rot.step.plan.as_dict(), "kv_copies_rotated": len(rot.pools),
+        "launches_per_step": 2,
+        "roofline": roofline_of(case, t, W.CONFIG_NAMES[idx]),
     }
-    if want_detail:
-        res["split_kernel_avg_s"] = kavg
-        res["split_kernel_median_s"] = kmed
     assert rot.step.dev_status() == 0
     return case, rot, res
 
@@ -411,13 +449,13 @@ def main():
     B.lib()   # fail loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
-    case, rot, main_res = bench_config(args.config, args, True)
+    case, rot, main_res = bench_config(args.config, args)
     kbytes = main_res["kv_bytes"]
-    achieved = kbytes / main_res["split_kernel_avg_s"] / 1e9
     line = {
         "metric": "verify-step attention: achieved HBM GB/s over algorithmic KV bytes (us per step in ms_per_step)",
         "value": main_res["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": main_res["us_per_step"] / 1e3, "us_per_step": main_res["us_per_step"],
+        "step_us": main_res["step_us"],
         "frac_of_hbm_peak": main_res["frac_of_hbm_peak"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {W.DT_BF16: "bf16", W.DT_F32: "f32", W.DT_F16: "f16"}[case.dtype], "data": "synthetic",
@@ -425,38 +463,36 @@ def main():
                    "ctx_lens_max": int(case.ctx_lens.max()), "ctx_tokens_total": int(case.ctx_lens.sum()),
                    "n_draft": case.N, "n_q_heads": case.Hq, "n_kv_heads": case.Hkv, "head_dim": case.D,
                    "page_size": 16, "kv_bytes_per_step": kbytes, "kv_copies_rotated": main_res["kv_copies_rotated"],
-                   "plan": main_res["plan"]},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(main_res["workload"]),
-                     "kernel": "splitkv_kernel", "kernel_avg_us": main_res["split_kernel_avg_s"] * 1e6,
-                     "kernel_median_us": main_res["split_kernel_median_s"] * 1e6,
-                     "algorithmic_bytes_per_launch": kbytes},
+                   "launches_per_step": main_res["launches_per_step"], "plan": main_res["plan"]},
+        "roofline": main_res["roofline"],
     }
-    # the same kernel against the matrix pipe: QK^T and PV are 2*D flop each per (row, key); the
-    # long-context tree shapes sit at the ridge between the two roofs
-    rows_per_kv = (case.Hq // case.Hkv) * case.N
-    flop = 4.0 * case.D * rows_per_kv * case.Hkv * float((case.ctx_lens.astype("int64") + case.N).sum())
-    line["roofline"]["mfma"] = {"achieved": flop / main_res["split_kernel_avg_s"] / 1e12, "peak": 2500.0,
-                                "unit": "TFLOP/s", "frac": flop / main_res["split_kernel_avg_s"] / 2.5e15,
-                                "algorithmic_flop_per_launch": flop}
     if not args.no_probe:
-        line["roofline"]["stream_read_probe_GBps"] = stream_probe_gbs()
+        rl = line["roofline"]
+        rl["stream_read_probe_GBps"] = stream_probe_gbs()
         # the chip is power-limited: the shader clock under load, read inside the kernels, next to the rates
-        line["roofline"]["shader_clock_GHz"] = {"nominal": 2.4, "splitkv_kernel": kernel_shader_clock(rot)}
+        rl["shader_clock_GHz"] = {"nominal": 2.4, "splitkv_kernel": kernel_shader_clock(rot)}
         for kind, key in (("random", "probe_random_operands"), ("ones", "probe_constant_operands")):
             tf, ghz = mfma_probe_tflops(kind)
-            line["roofline"]["mfma"][key + "_TFLOPs"] = tf
-            line["roofline"]["shader_clock_GHz"]["mfma_" + key] = ghz
-    if args.all:
+            rl["mfma"][key + "_TFLOPs"] = tf
+            rl["shader_clock_GHz"]["mfma_" + key] = ghz
+        # the same kernel time against what this very box sustained in the probes of this run
+        ksec = rl["kernel_avg_us"] * 1e-6
+        floor = max(kbytes / (rl["stream_read_probe_GBps"] * 1e9),
+                    rl["mfma"]["algorithmic_flop_per_launch"] / (rl["mfma"]["probe_random_operands_TFLOPs"] * 1e12))
+        rl["frac_of_measured_ceiling"] = floor / ksec
+        rl["measured_ceiling"] = ("the longer of: algorithmic bytes / streaming-read probe rate, algorithmic flop / "
+                                  "matrix-pipe probe rate on random operands, both from this run")
+    if not args.no_others:
         others = []
         for idx in (1, 2, 3, 4):
             if idx == args.config:
                 continue
             del rot
             torch.cuda.empty_cache()
-            _, rot, r = bench_config(idx, args, True)
+            _, rot, r = bench_config(idx, args)
             others.append(r)
         line["others"] = others
+    if args.all:
         line["step_kernels"] = bench_steps()
     if args.draft_sweep:
         line["draft_count_sweep"] = bench_draft_sweep()

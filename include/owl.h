@@ -91,9 +91,12 @@ typedef struct owl_verify_desc {
     int32_t split_tokens;       /* 0 = let the library choose; else tokens per KV split  */
                                 /* (rounded up to a multiple of 64) -- testing / tuning   */
     float scale;                /* multiplies q.k before the softmax, e.g. 1/sqrt(D)     */
-    int32_t reserved_;          /* set to 0                                              */
+    int32_t out_dtype;          /* owl_dtype of `out`: OWL_F32, or OWL_BF16 / OWL_F16 =  */
+                                /* the fp32 result rounded to nearest even on the way out */
     int64_t kv_stride_page, kv_stride_head, kv_stride_token;
     int64_t n_pool_pages;       /* pages in k_cache / v_cache (bounds for page ids)      */
+    int32_t flags;              /* no flag is defined: set to 0                          */
+    int32_t reserved_;          /* set to 0                                              */
 } owl_verify_desc;
 
 /* What the library decided for a descriptor; informational (bench, tests). */
@@ -112,6 +115,7 @@ typedef struct owl_plan {
     int32_t tiles_per_wave;  /* row tiles held in one wavefront's accumulators             */
     int32_t kernel_variant;  /* internal id of the instantiated split-KV kernel            */
     int32_t n_workgroups;    /* grid size of the split-KV pass                             */
+    int32_t reserved_;       /* 0                                                          */
     size_t workspace_bytes;
 } owl_plan;
 
@@ -138,7 +142,7 @@ owl_status owl_verify_attn_workspace_size(const owl_verify_desc *desc, size_t *b
  *                every sequence is physical page p; only sensible for B == 1)
  *   ctx_lens     [B] int32, prefix lengths, drafts not counted, 0 allowed
  *   tree_parent  [B][N] int32, -1 = root, else an index < i
- *   out          [B][N][Hq][D] float32, contiguous, fully overwritten
+ *   out          [B][N][Hq][D] in desc->out_dtype, contiguous, fully overwritten
  *   workspace    >= owl_verify_attn_workspace_size() bytes, 256-byte aligned;
  *                contents need no initialisation and are garbage afterwards
  *   dev_status   optional uint32 on the device, OR-ed with OWL_DEV_* bits;
@@ -147,7 +151,7 @@ owl_status owl_verify_attn_workspace_size(const owl_verify_desc *desc, size_t *b
  */
 owl_status owl_verify_attn(const owl_verify_desc *desc, const void *q, const void *k_cache,
                            const void *v_cache, const int32_t *page_table,
-                           const int32_t *ctx_lens, const int32_t *tree_parent, float *out,
+                           const int32_t *ctx_lens, const int32_t *tree_parent, void *out,
                            void *workspace, size_t workspace_bytes, uint32_t *dev_status,
                            void *stream);
 
@@ -184,7 +188,7 @@ owl_status owl_verify_attn_init(const owl_verify_desc *desc);
 #define OWL_NOALLOC_SCRATCH_BYTES (48u << 20)
 owl_status owl_verify_attn_noalloc(const owl_verify_desc *desc, const void *q, const void *k_cache,
                                    const void *v_cache, const int32_t *page_table,
-                                   const int32_t *ctx_lens, const int32_t *tree_parent, float *out,
+                                   const int32_t *ctx_lens, const int32_t *tree_parent, void *out,
                                    uint32_t *dev_status, void *stream);
 
 /*
@@ -200,7 +204,7 @@ owl_status owl_verify_attn_noalloc(const owl_verify_desc *desc, const void *q, c
 #define OWL_PHASE_ALL 3
 owl_status owl_verify_attn_phases(const owl_verify_desc *desc, const void *q, const void *k_cache,
                                   const void *v_cache, const int32_t *page_table,
-                                  const int32_t *ctx_lens, const int32_t *tree_parent, float *out,
+                                  const int32_t *ctx_lens, const int32_t *tree_parent, void *out,
                                   void *workspace, size_t workspace_bytes, uint32_t *dev_status,
                                   void *stream, int32_t phases);
 
@@ -217,7 +221,7 @@ owl_status owl_verify_attn_phases(const owl_verify_desc *desc, const void *q, co
 owl_status owl_verify_attn_ragged(const owl_verify_desc *desc, const void *q, const void *k_cache,
                                   const void *v_cache, const int32_t *page_table,
                                   const int32_t *ctx_lens, const int32_t *tree_parent,
-                                  const int32_t *n_draft_seq, float *out, void *workspace,
+                                  const int32_t *n_draft_seq, void *out, void *workspace,
                                   size_t workspace_bytes, uint32_t *dev_status, void *stream);
 
 /*
@@ -409,61 +413,6 @@ owl_status owl_build_tree_mask_host(const int32_t *tree_parent_host, int32_t n_d
 owl_status owl_gather_kv(const owl_verify_desc *desc, const void *cache,
                          const int32_t *page_table, int32_t seq, int64_t first_pos,
                          int64_t n_tokens, void *dst, uint32_t *dev_status, void *stream);
-
-/*
- * Measurement aid: a plain streaming read of `bytes` bytes (multiple of 16,
- * 16-byte aligned) with 128-bit loads by `n_workgroups` workgroups of 256
- * threads; every workgroup XOR-folds what it read into sink[workgroup] (uint32,
- * device).  Its achieved GB/s is the practical ceiling the split-KV pass is
- * compared with next to the nominal HBM peak.
- */
-owl_status owl_stream_read_probe(const void *src, size_t bytes, uint32_t *sink,
-                                 int32_t n_workgroups, void *stream);
-
-/*
- * Measurement aid: the sustained rate of the matrix pipe.  n_workgroups
- * workgroups of 8 wavefronts issue `iters` x 16 bf16 16x16x32 MFMAs per lane on
- * operands read once from src (`bytes` bytes, a multiple of 16, 16-byte aligned,
- * interpreted as bf16 values; their bit patterns matter: under its power limit
- * this chip sustains a lower rate on random values than on constants).  Flop =
- * n_workgroups * 8 * iters * 16 * 16384.  sink: n_workgroups * 512 floats, device.
- * clock_ghz: optional, n_workgroups floats, device: the shader clock every
- * workgroup ran at over its loop (shader cycles per constant-rate 100 MHz tick),
- * which shows the throttling directly.
- */
-owl_status owl_mfma_probe(const void *src, size_t bytes, int32_t iters, float *sink, float *clock_ghz,
-                          int32_t n_workgroups, void *stream);
-
-/*
- * Measurement aid: like owl_stream_read_probe, but the buffer is read in
- * 4 KiB blocks in the order block_order[0 .. n_blocks-1] (device int32, every
- * entry in [0, buffer bytes / 4096)).  With a random order this is the access
- * pattern of a head-major cache with 16-token pages of 128 bf16 channels
- * handed out at random, and its GB/s is the ceiling for that layout.
- */
-owl_status owl_gather_read_probe(const void *src, const int32_t *block_order, int32_t n_blocks,
-                                 uint32_t *sink, int32_t n_workgroups, void *stream);
-
-/*
- * Self-test of the cross-lane step of the in-kernel softmax: one wavefront
- * reads in64[64] and writes, for every lane l, the maximum over the lanes
- * {l, l^16, l^32, l^48} (the four lanes that hold the keys of one query row in
- * a 16x16 MFMA accumulator tile) to out64[64].  Device pointers.
- */
-owl_status owl_selftest_quad_max(const float *in64, float *out64, void *stream);
-
-/*
- * Profiling aid.  With a non-NULL device buffer of 10 * n_workgroups int64,
- * every workgroup of the split-KV pass of later owl_verify_attn calls records
- * the GPU's constant-rate (100 MHz) wall clock at: [0] entry, [1] page list and
- * tree mask ready, [2] first stage in LDS, [3] end of the fast loop, [4] end of
- * the careful loop, [5] partials written; [6] = (XCC id << 16) | CU id, [7] = its flat
- * workgroup index; [8], [9] = the shader cycle counter at [2] and [3], so that
- * ([9] - [8]) / ([3] - [2]) / 10 is the shader clock in GHz the workgroup really
- * ran its main loop at.  NULL (the default) switches recording off.  Not
- * thread-safe; meant for one measuring process.
- */
-owl_status owl_debug_set_timeline(long long *buffer);
 
 /* Static string for a status code. */
 const char *owl_status_str(owl_status s);

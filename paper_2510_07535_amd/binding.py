@@ -23,16 +23,21 @@ OWL_DEV_BAD_TOKEN, OWL_DEV_BAD_ROW = 32, 64
 OWL_DRAFTER_PROJ, OWL_DRAFTER_GATES, OWL_DRAFTER_ALL = 1, 2, 3
 OWL_W_ROWS, OWL_W_TILED = 0, 1
 
+# entry points declared in include/owl.h (the product interface) ...
 EXPORTS = (
     "owl_verify_attn_plan", "owl_verify_attn_workspace_size", "owl_verify_attn",
-    "owl_verify_attn_phases", "owl_stream_read_probe", "owl_selftest_quad_max",
-    "owl_gather_read_probe", "owl_debug_set_timeline", "owl_mfma_probe",
+    "owl_verify_attn_phases",
     "owl_build_tree_mask", "owl_build_tree_mask_host", "owl_gather_kv",
     "owl_prepare_spec_tree", "owl_accept_greedy", "owl_commit_kv", "owl_verify_attn_ragged",
     "owl_drafter_cell", "owl_drafter_cell_phases", "owl_drafter_cell_workspace_size", "owl_drafter_alpha",
     "owl_drafter_tiled_weight_bytes", "owl_drafter_tile_weights",
     "owl_verify_attn_init", "owl_verify_attn_noalloc",
     "owl_status_str", "owl_version",
+)
+# ... and in include/owl_probe.h (measurement and self-test aids)
+PROBE_EXPORTS = (
+    "owl_stream_read_probe", "owl_gather_read_probe", "owl_mfma_probe", "owl_selftest_quad_max",
+    "owl_debug_set_timeline",
 )
 OWL_NOALLOC_SCRATCH_BYTES = 48 << 20
 
@@ -45,9 +50,10 @@ class VerifyDesc(ctypes.Structure):
         ("head_dim", ctypes.c_int32), ("page_size", ctypes.c_int32),
         ("max_pages_per_seq", ctypes.c_int32), ("max_ctx_len", ctypes.c_int32),
         ("qkv_dtype", ctypes.c_int32), ("split_tokens", ctypes.c_int32),
-        ("scale", ctypes.c_float), ("reserved_", ctypes.c_int32),
+        ("scale", ctypes.c_float), ("out_dtype", ctypes.c_int32),
         ("kv_stride_page", ctypes.c_int64), ("kv_stride_head", ctypes.c_int64),
         ("kv_stride_token", ctypes.c_int64), ("n_pool_pages", ctypes.c_int64),
+        ("flags", ctypes.c_int32), ("reserved_", ctypes.c_int32),
     ]
 
 
@@ -58,6 +64,7 @@ class Plan(ctypes.Structure):
         ("rows_per_kv", ctypes.c_int32), ("row_tiles", ctypes.c_int32),
         ("row_groups", ctypes.c_int32), ("tiles_per_wave", ctypes.c_int32),
         ("kernel_variant", ctypes.c_int32), ("n_workgroups", ctypes.c_int32),
+        ("reserved_", ctypes.c_int32),
         ("workspace_bytes", ctypes.c_size_t),
     ]
 
@@ -119,7 +126,7 @@ def lib() -> ctypes.CDLL:
         l.owl_gather_read_probe.restype = ctypes.c_int
         l.owl_gather_read_probe.argtypes = [vp, vp, i32, vp, i32, vp]
         l.owl_debug_set_timeline.restype = ctypes.c_int
-        l.owl_debug_set_timeline.argtypes = [vp]
+        l.owl_debug_set_timeline.argtypes = [vp, i64]
         l.owl_selftest_quad_max.restype = ctypes.c_int
         l.owl_selftest_quad_max.argtypes = [vp, vp, vp]
         l.owl_build_tree_mask.restype = ctypes.c_int
@@ -173,13 +180,13 @@ def _stream() -> int:
 
 def make_desc(*, batch, n_draft, n_q_heads, n_kv_heads, head_dim, max_pages_per_seq, max_ctx_len,
               qkv_dtype, scale, kv_stride_page, kv_stride_head, kv_stride_token, n_pool_pages,
-              page_size=16, split_tokens=0) -> VerifyDesc:
+              page_size=16, split_tokens=0, out_dtype=OWL_F32, flags=0) -> VerifyDesc:
     return VerifyDesc(batch=batch, n_draft=n_draft, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads,
                       head_dim=head_dim, page_size=page_size, max_pages_per_seq=max_pages_per_seq,
                       max_ctx_len=max_ctx_len, qkv_dtype=qkv_dtype, split_tokens=split_tokens,
-                      scale=scale, reserved_=0, kv_stride_page=kv_stride_page,
+                      scale=scale, out_dtype=out_dtype, kv_stride_page=kv_stride_page,
                       kv_stride_head=kv_stride_head, kv_stride_token=kv_stride_token,
-                      n_pool_pages=n_pool_pages)
+                      n_pool_pages=n_pool_pages, flags=flags, reserved_=0)
 
 
 def owl_verify_attn_plan(desc: VerifyDesc) -> Plan:
@@ -247,8 +254,10 @@ def owl_gather_read_probe(src, block_order, sink, n_workgroups: int, stream: Opt
 
 
 def owl_debug_set_timeline(buffer) -> None:
-    """buffer: int64 CUDA tensor with 8 entries per split-KV workgroup, or None to switch off."""
-    _check(lib().owl_debug_set_timeline(_ptr(buffer)), "owl_debug_set_timeline")
+    """buffer: int64 CUDA tensor with 10 entries per split-KV workgroup (its length gives the
+    number of workgroups it has room for), or None to switch the recording off."""
+    n = 0 if buffer is None else int(buffer.numel()) // 10
+    _check(lib().owl_debug_set_timeline(_ptr(buffer), n), "owl_debug_set_timeline")
 
 
 def owl_selftest_quad_max(in64, out64, stream: Optional[int] = None) -> None:

@@ -12,7 +12,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OUT = os.path.join(PKG, "libowl.so")
 OBJ = os.path.join(PKG, "_build")
-SOURCES = ["owl_splitkv.hip", "owl_aux.hip", "owl_steps.hip", "owl_drafter.hip", "owl_api.hip"]
+SOURCES = ["owl_splitkv.hip", "owl_aux.hip", "owl_steps.hip", "owl_drafter.hip", "owl_probe.hip", "owl_api.hip"]
 
 # -packed-fp32-ops is switched OFF on purpose: packed fp32 VALU forms are not
 # to be generated for this target (hipcc's host pass does not know the feature

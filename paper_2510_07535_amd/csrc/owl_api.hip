@@ -42,6 +42,8 @@ owl_status check_desc(const owl_verify_desc *d)
     if (d->max_ctx_len < 0 || d->max_ctx_len > (1 << 30)) return OWL_ERR_INVALID_ARG;
     if (d->max_pages_per_seq < 0 || d->n_pool_pages < 1) return OWL_ERR_INVALID_ARG;
     if (d->split_tokens < 0) return OWL_ERR_INVALID_ARG;
+    if (d->out_dtype != OWL_F32 && d->out_dtype != OWL_BF16 && d->out_dtype != OWL_F16) return OWL_ERR_UNSUPPORTED;
+    if (d->flags != 0 || d->reserved_ != 0) return OWL_ERR_INVALID_ARG;
     if (!(d->scale > 0.0f) || !isfinite(d->scale)) return OWL_ERR_INVALID_ARG;
     const int es = elem_size(d->qkv_dtype);
     const int64_t st[3] = {d->kv_stride_page, d->kv_stride_head, d->kv_stride_token};
@@ -176,8 +178,6 @@ owl_status ensure_lds_attr(const Variant *v)
     return OWL_OK;
 }
 
-long long *g_timeline = nullptr;   // set by owl_debug_set_timeline
-
 // Device memory of owl_verify_attn_noalloc: the split partials live here instead of in a
 // caller's workspace.  One copy per GPU that loads the library, held until the process ends.
 // In host code the array's name is only a handle: its device address comes from
@@ -229,7 +229,7 @@ owl_status owl_verify_attn_workspace_size(const owl_verify_desc *desc, size_t *b
 
 owl_status owl_verify_attn(const owl_verify_desc *desc, const void *q, const void *k_cache,
                            const void *v_cache, const int32_t *page_table,
-                           const int32_t *ctx_lens, const int32_t *tree_parent, float *out,
+                           const int32_t *ctx_lens, const int32_t *tree_parent, void *out,
                            void *workspace, size_t workspace_bytes, uint32_t *dev_status,
                            void *stream)
 {
@@ -239,13 +239,13 @@ owl_status owl_verify_attn(const owl_verify_desc *desc, const void *q, const voi
 
 static owl_status verify_impl(const owl_verify_desc *desc, const void *q, const void *k_cache,
                               const void *v_cache, const int32_t *page_table, const int32_t *ctx_lens,
-                              const int32_t *tree_parent, const int32_t *n_draft_seq, float *out,
+                              const int32_t *tree_parent, const int32_t *n_draft_seq, void *out,
                               void *workspace, size_t workspace_bytes, uint32_t *dev_status, void *stream,
                               int32_t phases);
 
 owl_status owl_verify_attn_phases(const owl_verify_desc *desc, const void *q, const void *k_cache,
                                   const void *v_cache, const int32_t *page_table,
-                                  const int32_t *ctx_lens, const int32_t *tree_parent, float *out,
+                                  const int32_t *ctx_lens, const int32_t *tree_parent, void *out,
                                   void *workspace, size_t workspace_bytes, uint32_t *dev_status,
                                   void *stream, int32_t phases)
 {
@@ -256,7 +256,7 @@ owl_status owl_verify_attn_phases(const owl_verify_desc *desc, const void *q, co
 owl_status owl_verify_attn_ragged(const owl_verify_desc *desc, const void *q, const void *k_cache,
                                   const void *v_cache, const int32_t *page_table,
                                   const int32_t *ctx_lens, const int32_t *tree_parent,
-                                  const int32_t *n_draft_seq, float *out, void *workspace,
+                                  const int32_t *n_draft_seq, void *out, void *workspace,
                                   size_t workspace_bytes, uint32_t *dev_status, void *stream)
 {
     if (!n_draft_seq) return OWL_ERR_INVALID_ARG;
@@ -266,7 +266,7 @@ owl_status owl_verify_attn_ragged(const owl_verify_desc *desc, const void *q, co
 
 static owl_status verify_impl(const owl_verify_desc *desc, const void *q, const void *k_cache,
                               const void *v_cache, const int32_t *page_table, const int32_t *ctx_lens,
-                              const int32_t *tree_parent, const int32_t *n_draft_seq, float *out,
+                              const int32_t *tree_parent, const int32_t *n_draft_seq, void *out,
                               void *workspace, size_t workspace_bytes, uint32_t *dev_status, void *stream,
                               int32_t phases)
 {
@@ -283,17 +283,28 @@ static owl_status verify_impl(const owl_verify_desc *desc, const void *q, const 
     if (!workspace || workspace_bytes < fp.pub.workspace_bytes) return OWL_ERR_WORKSPACE;
     if (misaligned(workspace, 256)) return OWL_ERR_INVALID_ARG;
 
-    st = ensure_lds_attr(fp.variant);
+    // the profiling copy of the kernel, if the timeline hook is on and has room for this grid
+    const Variant *variant = fp.variant;
+    const TimelineHook hook = timeline_hook();
+    if (hook.buffer && fp.pub.n_workgroups <= hook.capacity) {
+        const Variant *tv = find_variant(variant->dtype, variant->D, variant->tpw, variant->wr, variant->wk, true);
+        if (tv) variant = tv;
+    }
+    st = ensure_lds_attr(variant);
     if (st != OWL_OK) return st;
 
+    // workspace: partial O | partial (m, l) | derived split size
+    char *ws = static_cast<char *>(workspace);
     KParams p;
     memset(&p, 0, sizeof p);
     p.q = q; p.k = k_cache; p.v = v_cache;
     p.page_table = page_table; p.ctx_lens = ctx_lens; p.parent = tree_parent;
     p.n_draft_seq = n_draft_seq;
-    p.part_o = static_cast<float *>(workspace);
-    p.part_ml = reinterpret_cast<float *>(static_cast<char *>(workspace) + fp.part_o_bytes);
+    p.part_o = reinterpret_cast<float *>(ws);
+    p.part_ml = reinterpret_cast<float *>(ws + fp.part_o_bytes);
+    p.dev_c = reinterpret_cast<int32_t *>(ws + fp.part_o_bytes + fp.part_ml_bytes);
     p.out = out;
+    p.out_dtype = desc->out_dtype;
     p.dev_status = dev_status;
     p.B = desc->batch; p.N = desc->n_draft; p.Hq = desc->n_q_heads; p.Hkv = desc->n_kv_heads;
     p.G = p.Hq / p.Hkv; p.R = fp.pub.rows_per_kv;
@@ -301,18 +312,17 @@ static owl_status verify_impl(const owl_verify_desc *desc, const void *q, const 
     p.C = fp.pub.split_tokens; p.max_splits = fp.pub.max_splits;
     p.adapt = fp.adapt; p.c_min = fp.c_min;
     p.n_cu = device_cus();
-    p.dev_c = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + fp.part_o_bytes + fp.part_ml_bytes);
     p.RT = fp.pub.row_tiles; p.row_groups = fp.pub.row_groups;
     p.stride_page = desc->kv_stride_page; p.stride_head = desc->kv_stride_head;
     p.stride_token = desc->kv_stride_token; p.n_pool_pages = desc->n_pool_pages;
     p.c_log2 = desc->scale * 1.4426950408889634f;
-    p.timeline = g_timeline;
+    p.timeline = variant->timeline ? hook.buffer : nullptr;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     p.item_slots = (int32_t)fp.item_slots;
     const dim3 grid = fp.grid;
     if (phases & OWL_PHASE_SPLIT) {
-        fp.variant->launch(p, grid, s);
+        variant->launch(p, grid, s);
         if (hipGetLastError() != hipSuccess) return OWL_ERR_HIP;
     }
     if (phases & OWL_PHASE_COMBINE)
@@ -327,13 +337,14 @@ owl_status owl_verify_attn_init(const owl_verify_desc *desc)
     if (st != OWL_OK) return st;
     st = ensure_lds_attr(fp.variant);
     if (st != OWL_OK) return st;
+    if (load_aux_kernels() != hipSuccess) return OWL_ERR_HIP;
     void *ptr = nullptr;
     return scratch_address(&ptr);
 }
 
 owl_status owl_verify_attn_noalloc(const owl_verify_desc *desc, const void *q, const void *k_cache,
                                    const void *v_cache, const int32_t *page_table, const int32_t *ctx_lens,
-                                   const int32_t *tree_parent, float *out, uint32_t *dev_status, void *stream)
+                                   const int32_t *tree_parent, void *out, uint32_t *dev_status, void *stream)
 {
     FullPlan fp;
     owl_status st = make_plan(desc, &fp);
@@ -530,53 +541,6 @@ owl_status owl_gather_kv(const owl_verify_desc *desc, const void *cache, const i
     return OWL_OK;
 }
 
-owl_status owl_stream_read_probe(const void *src, size_t bytes, uint32_t *sink,
-                                 int32_t n_workgroups, void *stream)
-{
-    if (!src || !sink || n_workgroups < 1 || bytes % 16 != 0) return OWL_ERR_INVALID_ARG;
-    if (misaligned(src, 16)) return OWL_ERR_INVALID_ARG;
-    if (launch_stream_read(src, bytes, sink, n_workgroups, static_cast<hipStream_t>(stream)) != hipSuccess)
-        return OWL_ERR_HIP;
-    return OWL_OK;
-}
-
-owl_status owl_mfma_probe(const void *src, size_t bytes, int32_t iters, float *sink, float *clock_ghz,
-                          int32_t n_workgroups, void *stream)
-{
-    if (!src || !sink || n_workgroups < 1 || iters < 1 || bytes < 16 || bytes % 16 != 0 ||
-        bytes / 16 > 0x7fffffff)
-        return OWL_ERR_INVALID_ARG;
-    if (misaligned(src, 16)) return OWL_ERR_INVALID_ARG;
-    if (launch_mfma_probe(src, bytes, iters, sink, clock_ghz, n_workgroups, static_cast<hipStream_t>(stream)) !=
-        hipSuccess)
-        return OWL_ERR_HIP;
-    return OWL_OK;
-}
-
-owl_status owl_gather_read_probe(const void *src, const int32_t *block_order, int32_t n_blocks,
-                                 uint32_t *sink, int32_t n_workgroups, void *stream)
-{
-    if (!src || !block_order || !sink || n_blocks < 1 || n_workgroups < 1) return OWL_ERR_INVALID_ARG;
-    if (misaligned(src, 16)) return OWL_ERR_INVALID_ARG;
-    if (launch_gather_read(src, block_order, n_blocks, sink, n_workgroups,
-                           static_cast<hipStream_t>(stream)) != hipSuccess)
-        return OWL_ERR_HIP;
-    return OWL_OK;
-}
-
-owl_status owl_debug_set_timeline(long long *buffer)
-{
-    g_timeline = buffer;
-    return OWL_OK;
-}
-
-owl_status owl_selftest_quad_max(const float *in64, float *out64, void *stream)
-{
-    if (!in64 || !out64) return OWL_ERR_INVALID_ARG;
-    if (launch_quad_max(in64, out64, static_cast<hipStream_t>(stream)) != hipSuccess) return OWL_ERR_HIP;
-    return OWL_OK;
-}
-
 const char *owl_status_str(owl_status s)
 {
     switch (s) {
@@ -591,6 +555,6 @@ const char *owl_status_str(owl_status s)
     return "unknown status";
 }
 
-const char *owl_version(void) { return "0.1"; }
+const char *owl_version(void) { return "0.2"; }
 
 }  // extern "C"

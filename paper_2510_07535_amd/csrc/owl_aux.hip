@@ -44,8 +44,8 @@ __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
     for (int u = 0; u < UPW; ++u) acc[u] = make_float4(0.f, 0.f, 0.f, 0.f);
     // The merge is a chain (each split rescales the running sums), the loads are not: the
     // partials of kInFlight splits are requested together, so that a wavefront pays the
-    // memory latency once per batch rather than once per split.
-    constexpr int kInFlight = 4;
+    // memory latency once per batch rather than once per split (up to 32 splits: once).
+    constexpr int kInFlight = 8;
     for (int s0 = w; s0 < ns; s0 += 4 * kInFlight) {
         float ms[kInFlight], ls[kInFlight];
         float4 x[kInFlight][UPW];
@@ -102,12 +102,13 @@ __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
     if (row >= p.R) return;
     const int i = row / p.G, hh = row % p.G;
     const float inv = i < Nb ? 1.0f / lsum : 0.f;                   // rows of absent nodes come out as zeros
-    float *o = p.out + (((int64_t)b * p.N + i) * p.Hq + g * p.G + hh) * D + 4 * qd;
+    const int64_t o = (((int64_t)b * p.N + i) * p.Hq + g * p.G + hh) * D + 4 * qd;
 #pragma unroll
     for (int u = 0; u < UPW; ++u)
-        *reinterpret_cast<float4 *>(o + 16 * (u0 + u)) =
-            i < Nb ? make_float4(tot[u].x * inv, tot[u].y * inv, tot[u].z * inv, tot[u].w * inv)
-                   : make_float4(0.f, 0.f, 0.f, 0.f);
+        store_out4(p.out, o + 16 * (u0 + u),
+                   i < Nb ? make_float4(tot[u].x * inv, tot[u].y * inv, tot[u].z * inv, tot[u].w * inv)
+                          : make_float4(0.f, 0.f, 0.f, 0.f),
+                   p.out_dtype);
 }
 
 hipError_t launch_combine(const KParams &p, int D, hipStream_t s)
@@ -189,120 +190,14 @@ hipError_t launch_gather(const owl_verify_desc &d, const void *cache, const int3
     return hipGetLastError();
 }
 
-// ---------------------------------------------------------------------------
-// Streaming-read probe: each workgroup walks the buffer in 4 KiB slabs
-// (256 threads x 16 bytes), workgroups interleaved slab by slab.
-// ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) stream_read_kernel(const uint4 *src, size_t n_vec, uint32_t *sink)
+// Makes the runtime resolve the combine kernels now, so that their first launch may happen
+// inside a stream capture.
+hipError_t load_aux_kernels()
 {
-    uint32_t acc = 0;
-    const size_t stride = (size_t)gridDim.x * 256;
-    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    for (; i + 3 * stride < n_vec; i += 4 * stride) {
-        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
-    }
-    for (; i < n_vec; i += stride) {
-        const uint4 a = src[i];
-        acc ^= a.x ^ a.y ^ a.z ^ a.w;
-    }
-    for (int off = 32; off > 0; off >>= 1) acc ^= __shfl_xor(acc, off);
-    __shared__ uint32_t s_acc[4];
-    if ((threadIdx.x & 63) == 0) s_acc[threadIdx.x >> 6] = acc;
-    __syncthreads();
-    if (threadIdx.x == 0) sink[blockIdx.x] = s_acc[0] ^ s_acc[1] ^ s_acc[2] ^ s_acc[3];
-}
-
-// Same, but the buffer is visited in 4 KiB blocks in the order given by
-// `perm` (one block = 256 threads x 16 bytes), eight blocks in flight per
-// workgroup: the access pattern of a head-major paged cache whose pages were
-// handed out in random order.
-__global__ void __launch_bounds__(256) gather_read_kernel(const uint4 *src, const int32_t *perm,
-                                                          int n_blocks, uint32_t *sink)
-{
-    uint32_t acc = 0;
-    int blk = blockIdx.x;
-    const int stride = gridDim.x;
-    for (; blk + 7 * stride < n_blocks; blk += 8 * stride) {
-        uint4 v[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = src[(size_t)perm[blk + i * stride] * 256 + threadIdx.x];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc ^= v[i].x ^ v[i].y ^ v[i].z ^ v[i].w;
-    }
-    for (; blk < n_blocks; blk += stride) {
-        const uint4 a = src[(size_t)perm[blk] * 256 + threadIdx.x];
-        acc ^= a.x ^ a.y ^ a.z ^ a.w;
-    }
-    for (int off = 32; off > 0; off >>= 1) acc ^= __shfl_xor(acc, off);
-    __shared__ uint32_t s_acc[4];
-    if ((threadIdx.x & 63) == 0) s_acc[threadIdx.x >> 6] = acc;
-    __syncthreads();
-    if (threadIdx.x == 0) sink[blockIdx.x] = s_acc[0] ^ s_acc[1] ^ s_acc[2] ^ s_acc[3];
-}
-
-hipError_t launch_gather_read(const void *src, const int32_t *perm, int n_blocks, uint32_t *sink,
-                              int n_wg, hipStream_t s)
-{
-    hipLaunchKernelGGL(gather_read_kernel, dim3(n_wg), dim3(256), 0, s,
-                       static_cast<const uint4 *>(src), perm, n_blocks, sink);
-    return hipGetLastError();
-}
-
-// ---------------------------------------------------------------------------
-// Matrix-pipe probe: 8 wavefronts per workgroup, each issuing nothing but
-// 16x16x32 bf16 MFMAs on operands taken once from `src` (so their bit patterns
-// are the caller's: the sustained rate of this chip depends on them).  16
-// independent accumulators per lane; sums are scaled down now and then to stay
-// finite.  2 * 16*16*32 flop per MFMA, 16 MFMAs per lane and iteration.
-// ---------------------------------------------------------------------------
-typedef float probe_f32x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
-
-__global__ void __launch_bounds__(512) mfma_probe_kernel(const uint4 *src, int n_vec, int iters, float *sink,
-                                                         float *clock_ghz)
-{
-    uint4 a[8], b[2];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) a[i] = src[(threadIdx.x * 8 + i) % n_vec];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) b[i] = src[(threadIdx.x * 2 + i + 77) % n_vec];
-    probe_f32x4 acc[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = probe_f32x4{0.f, 0.f, 0.f, 0.f};
-    // shader cycles over constant-rate (100 MHz) ticks = the clock this workgroup really ran at
-    const long long c0 = clock64(), w0 = wall_clock64();
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(probe_bf16x8, a[i & 7]),
-                                                             __builtin_bit_cast(probe_bf16x8, b[i >> 3]), acc[i], 0, 0, 0);
-        if ((it & 63) == 63) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[i] *= 1.0e-3f;
-        }
-    }
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) s += acc[i][0] + acc[i][3];
-    sink[blockIdx.x * 512 + threadIdx.x] = s;
-    const long long c1 = clock64(), w1 = wall_clock64();
-    if (clock_ghz && threadIdx.x == 0) clock_ghz[blockIdx.x] = w1 > w0 ? (float)(c1 - c0) / ((float)(w1 - w0) * 10.0f) : 0.f;
-}
-
-hipError_t launch_mfma_probe(const void *src, size_t bytes, int iters, float *sink, float *clock_ghz, int n_wg,
-                             hipStream_t s)
-{
-    hipLaunchKernelGGL(mfma_probe_kernel, dim3(n_wg), dim3(512), 0, s, static_cast<const uint4 *>(src),
-                       (int)(bytes / 16), iters, sink, clock_ghz);
-    return hipGetLastError();
-}
-
-hipError_t launch_stream_read(const void *src, size_t bytes, uint32_t *sink, int n_wg, hipStream_t s)
-{
-    hipLaunchKernelGGL(stream_read_kernel, dim3(n_wg), dim3(256), 0, s,
-                       static_cast<const uint4 *>(src), bytes / 16, sink);
-    return hipGetLastError();
+    hipFuncAttributes a;
+    hipError_t e = hipFuncGetAttributes(&a, reinterpret_cast<const void *>(&combine_kernel<128>));
+    if (e == hipSuccess) e = hipFuncGetAttributes(&a, reinterpret_cast<const void *>(&combine_kernel<64>));
+    return e;
 }
 
 }  // namespace owl

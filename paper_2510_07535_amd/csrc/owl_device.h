@@ -10,6 +10,29 @@ __device__ __forceinline__ void flag_status(uint32_t *st, uint32_t bit)
     if (st) atomicOr(st, bit);
 }
 
+// Four consecutive output channels, starting at element index `e` of the output array, in the
+// output type: fp32 as it is, 16-bit types rounded to nearest even from the fp32 value.
+__device__ __forceinline__ void store_out4(void *out, int64_t e, float4 v, int out_dtype)
+{
+    typedef float o_f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 o_bf16x2 __attribute__((ext_vector_type(2)));
+    typedef _Float16 o_f16x2 __attribute__((ext_vector_type(2)));
+    if (out_dtype == OWL_F32) {
+        *reinterpret_cast<float4 *>(static_cast<float *>(out) + e) = v;
+        return;
+    }
+    const o_f32x2 lo = {v.x, v.y}, hi = {v.z, v.w};
+    uint2 w;
+    if (out_dtype == OWL_BF16) {
+        w.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, o_bf16x2));
+        w.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, o_bf16x2));
+    } else {
+        w.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, o_f16x2));
+        w.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, o_f16x2));
+    }
+    *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(out) + e) = w;
+}
+
 // Prefix length of sequence b, forced into [0, max_ctx_len].
 __device__ __forceinline__ int load_ctx_len(const int32_t *ctx_lens, int b, int max_ctx_len,
                                             uint32_t *st)
@@ -208,6 +231,20 @@ __device__ __forceinline__ uint64_t ancestor_set(const int32_t *parent, int i, i
     }
     if (depth_out) *depth_out = depth;
     return set;
+}
+
+// max over the four lanes {l, l^16, l^32, l^48}.  permlane32_swap(a, b) trades
+// a's upper 32 lanes against b's lower 32; permlane16_swap trades a's odd
+// 16-lane rows against b's even rows; fed with two copies of x, the two
+// results together hold x and its partner for every lane.
+__device__ __forceinline__ float quad_column_max(float v)
+{
+    const uint32_t x = __builtin_bit_cast(uint32_t, v);
+    auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    const float a = fmaxf(__builtin_bit_cast(float, (uint32_t)r[0]), __builtin_bit_cast(float, (uint32_t)r[1]));
+    const uint32_t y = __builtin_bit_cast(uint32_t, a);
+    auto r2 = __builtin_amdgcn_permlane16_swap(y, y, false, false);
+    return fmaxf(__builtin_bit_cast(float, (uint32_t)r2[0]), __builtin_bit_cast(float, (uint32_t)r2[1]));
 }
 
 }  // namespace owl

@@ -22,7 +22,8 @@ struct KParams {
     const int32_t *n_draft_seq;   // optional [B]: drafted tokens of each sequence (<= N), else null = N everywhere
     float *part_o;        // split partials: accumulator fragments
     float *part_ml;       // split partials: running reference m and row sum l
-    float *out;
+    void *out;            // [B][N][Hq][D] in out_dtype
+    int32_t out_dtype;    // OWL_F32, OWL_BF16 or OWL_F16
     uint32_t *dev_status;
     int32_t B, N, Hq, Hkv, G, R;
     int32_t max_pages, max_ctx_len;
@@ -37,19 +38,31 @@ struct KParams {
     int32_t row_groups;
     int64_t stride_page, stride_head, stride_token, n_pool_pages;
     float c_log2;         // scale * log2(e): scores live in the exp2 domain
-    long long *timeline;  // optional: 10 slots per workgroup (profiling aid), else null
+    long long *timeline;  // instantiations with the timeline hook only: 10 slots per workgroup (profiling aid)
 };
 
-// One instantiated split-KV kernel.
+// One instantiated split-KV kernel.  `timeline` marks the copies that carry the
+// per-workgroup timeline hook (profiling builds of the bf16 / D = 128 kernels);
+// the production copies have no trace of it.
 struct Variant {
     int dtype, D, tpw, wr, wk;
+    bool timeline;
     size_t lds_bytes;
     void (*launch)(const KParams &, dim3 grid, hipStream_t);
     const void *func;     // for hipFuncSetAttribute
 };
 
-const Variant *find_variant(int dtype, int D, int tpw, int wr, int wk);
+const Variant *find_variant(int dtype, int D, int tpw, int wr, int wk, bool timeline = false);
 int variant_index(const Variant *v);
+
+// Profiling hook state (set through the probe interface; read by the verify entry points).
+struct TimelineHook {
+    long long *buffer;    // device memory, 10 int64 per workgroup, or null
+    long long capacity;   // workgroups the buffer has room for
+};
+TimelineHook timeline_hook();
+void set_timeline_hook(long long *buffer, long long capacity);
+hipError_t load_aux_kernels();
 
 hipError_t launch_combine(const KParams &p, int D, hipStream_t s);
 hipError_t launch_prepare(const int32_t *parent, const int32_t *ctx_lens, int B, int n, int32_t *parent2,
@@ -75,12 +88,5 @@ hipError_t launch_tree_mask(const int32_t *parent, int B, int N, uint64_t *anc, 
 hipError_t launch_gather(const owl_verify_desc &d, const void *cache, const int32_t *page_table,
                          int seq, int64_t first, int64_t n, void *dst, uint32_t *status,
                          hipStream_t s);
-
-hipError_t launch_mfma_probe(const void *src, size_t bytes, int iters, float *sink, float *clock_ghz, int n_wg,
-                             hipStream_t s);
-hipError_t launch_gather_read(const void *src, const int32_t *perm, int n_blocks, uint32_t *sink,
-                              int n_wg, hipStream_t s);
-hipError_t launch_quad_max(const float *in, float *out, hipStream_t s);
-hipError_t launch_stream_read(const void *src, size_t bytes, uint32_t *sink, int n_wg, hipStream_t s);
 
 }  // namespace owl

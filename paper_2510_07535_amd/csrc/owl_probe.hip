@@ -1,0 +1,200 @@
+// Measurement and self-test aids of the verify-attention library: kernels that
+// measure what the chip can do (streaming reads, the matrix pipe), a one-wave
+// check of a cross-lane step, and the switch of the per-workgroup timeline
+// hook.  Declared in owl_probe.h; nothing here is on the product path.
+#include <atomic>
+
+#include "owl_device.h"
+#include "owl_probe.h"
+
+namespace owl {
+
+// ---------------------------------------------------------------------------
+// Streaming-read probe.  Every workgroup owns one contiguous piece of the
+// buffer and walks it front to back; a thread keeps 16 independent 16-byte
+// loads in flight (64 KiB per workgroup and round), the way the library's own
+// streaming kernels do.  What it reaches is the practical ceiling of a plain
+// HBM read on this chip.
+// ---------------------------------------------------------------------------
+constexpr int kStreamUnroll = 16;
+
+__global__ void __launch_bounds__(256) stream_read_kernel(const uint4 *__restrict__ src, size_t n_vec,
+                                                          uint32_t *sink)
+{
+    uint32_t acc = 0;
+    // piece of this workgroup: whole rounds of kStreamUnroll * 256 vectors, the remainder goes to the last one
+    const size_t round = (size_t)kStreamUnroll * 256;
+    const size_t rounds_total = n_vec / round;
+    const size_t per_wg = (rounds_total + gridDim.x - 1) / gridDim.x;
+    const size_t r0 = min(per_wg * blockIdx.x, rounds_total), r1 = min(r0 + per_wg, rounds_total);
+    for (size_t r = r0; r < r1; ++r) {
+        const uint4 *base = src + r * round + threadIdx.x;
+        uint4 v[kStreamUnroll];
+#pragma unroll
+        for (int k = 0; k < kStreamUnroll; ++k) v[k] = base[k * 256];
+#pragma unroll
+        for (int k = 0; k < kStreamUnroll; ++k) acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
+    }
+    if (blockIdx.x == gridDim.x - 1)
+        for (size_t i = rounds_total * round + threadIdx.x; i < n_vec; i += 256) {
+            const uint4 a = src[i];
+            acc ^= a.x ^ a.y ^ a.z ^ a.w;
+        }
+    for (int off = 32; off > 0; off >>= 1) acc ^= __shfl_xor(acc, off);
+    __shared__ uint32_t s_acc[4];
+    if ((threadIdx.x & 63) == 0) s_acc[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) sink[blockIdx.x] = s_acc[0] ^ s_acc[1] ^ s_acc[2] ^ s_acc[3];
+}
+
+// The buffer is visited in 4 KiB blocks in the order given by `perm` (one block
+// = 256 threads x 16 bytes), eight blocks in flight per workgroup: the access
+// pattern of a head-major paged cache whose pages were handed out in random
+// order.
+__global__ void __launch_bounds__(256) gather_read_kernel(const uint4 *src, const int32_t *perm,
+                                                          int n_blocks, uint32_t *sink)
+{
+    uint32_t acc = 0;
+    int blk = blockIdx.x;
+    const int stride = gridDim.x;
+    for (; blk + 7 * stride < n_blocks; blk += 8 * stride) {
+        uint4 v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = src[(size_t)perm[blk + i * stride] * 256 + threadIdx.x];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc ^= v[i].x ^ v[i].y ^ v[i].z ^ v[i].w;
+    }
+    for (; blk < n_blocks; blk += stride) {
+        const uint4 a = src[(size_t)perm[blk] * 256 + threadIdx.x];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w;
+    }
+    for (int off = 32; off > 0; off >>= 1) acc ^= __shfl_xor(acc, off);
+    __shared__ uint32_t s_acc[4];
+    if ((threadIdx.x & 63) == 0) s_acc[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) sink[blockIdx.x] = s_acc[0] ^ s_acc[1] ^ s_acc[2] ^ s_acc[3];
+}
+
+// ---------------------------------------------------------------------------
+// Matrix-pipe probe: 8 wavefronts per workgroup, each issuing nothing but
+// 16x16x32 bf16 MFMAs on operands taken once from `src` (so their bit patterns
+// are the caller's: the sustained rate of this chip depends on them).  16
+// independent accumulators per lane; sums are scaled down now and then to stay
+// finite.  2 * 16*16*32 flop per MFMA, 16 MFMAs per lane and iteration.
+// ---------------------------------------------------------------------------
+typedef float probe_f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
+
+__global__ void __launch_bounds__(512) mfma_probe_kernel(const uint4 *src, int n_vec, int iters, float *sink,
+                                                         float *clock_ghz)
+{
+    uint4 a[8], b[2];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a[i] = src[(threadIdx.x * 8 + i) % n_vec];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) b[i] = src[(threadIdx.x * 2 + i + 77) % n_vec];
+    probe_f32x4 acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = probe_f32x4{0.f, 0.f, 0.f, 0.f};
+    // shader cycles over constant-rate (100 MHz) ticks = the clock this workgroup really ran at
+    const long long c0 = clock64(), w0 = wall_clock64();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(probe_bf16x8, a[i & 7]),
+                                                             __builtin_bit_cast(probe_bf16x8, b[i >> 3]), acc[i], 0, 0, 0);
+        if ((it & 63) == 63) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] *= 1.0e-3f;
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += acc[i][0] + acc[i][3];
+    sink[blockIdx.x * 512 + threadIdx.x] = s;
+    const long long c1 = clock64(), w1 = wall_clock64();
+    if (clock_ghz && threadIdx.x == 0) clock_ghz[blockIdx.x] = w1 > w0 ? (float)(c1 - c0) / ((float)(w1 - w0) * 10.0f) : 0.f;
+}
+
+// One wavefront: out[l] = max over the lanes {l, l^16, l^32, l^48} of in[.].
+__global__ void __launch_bounds__(64) quad_max_kernel(const float *in, float *out)
+{
+    out[threadIdx.x] = quad_column_max(in[threadIdx.x]);
+}
+
+// ---------------------------------------------------------------------------
+// The timeline hook's switch: a pointer and a capacity, read by the verify
+// entry points at launch time.
+// ---------------------------------------------------------------------------
+static std::atomic<long long *> g_tl_buffer{nullptr};
+static std::atomic<long long> g_tl_capacity{0};
+
+TimelineHook timeline_hook()
+{
+    TimelineHook h;
+    h.capacity = g_tl_capacity.load(std::memory_order_acquire);
+    h.buffer = g_tl_buffer.load(std::memory_order_acquire);
+    return h;
+}
+
+void set_timeline_hook(long long *buffer, long long capacity)
+{
+    g_tl_buffer.store(nullptr, std::memory_order_release);       // never a pointer with the other buffer's size
+    g_tl_capacity.store(buffer ? capacity : 0, std::memory_order_release);
+    g_tl_buffer.store(buffer, std::memory_order_release);
+}
+
+}  // namespace owl
+
+using namespace owl;
+
+namespace {
+bool misaligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) % 16) != 0; }
+}  // namespace
+
+extern "C" {
+
+owl_status owl_stream_read_probe(const void *src, size_t bytes, uint32_t *sink, int32_t n_workgroups, void *stream)
+{
+    if (!src || !sink || n_workgroups < 1 || bytes % 16 != 0 || misaligned16(src)) return OWL_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(stream_read_kernel, dim3(n_workgroups), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint4 *>(src), bytes / 16, sink);
+    return hipGetLastError() == hipSuccess ? OWL_OK : OWL_ERR_HIP;
+}
+
+owl_status owl_gather_read_probe(const void *src, const int32_t *block_order, int32_t n_blocks, uint32_t *sink,
+                                 int32_t n_workgroups, void *stream)
+{
+    if (!src || !block_order || !sink || n_blocks < 1 || n_workgroups < 1 || misaligned16(src))
+        return OWL_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(gather_read_kernel, dim3(n_workgroups), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint4 *>(src), block_order, n_blocks, sink);
+    return hipGetLastError() == hipSuccess ? OWL_OK : OWL_ERR_HIP;
+}
+
+owl_status owl_mfma_probe(const void *src, size_t bytes, int32_t iters, float *sink, float *clock_ghz,
+                          int32_t n_workgroups, void *stream)
+{
+    if (!src || !sink || n_workgroups < 1 || iters < 1 || bytes < 16 || bytes % 16 != 0 ||
+        bytes / 16 > 0x7fffffff || misaligned16(src))
+        return OWL_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3(n_workgroups), dim3(512), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint4 *>(src), (int)(bytes / 16), iters, sink, clock_ghz);
+    return hipGetLastError() == hipSuccess ? OWL_OK : OWL_ERR_HIP;
+}
+
+owl_status owl_selftest_quad_max(const float *in64, float *out64, void *stream)
+{
+    if (!in64 || !out64) return OWL_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(quad_max_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), in64, out64);
+    return hipGetLastError() == hipSuccess ? OWL_OK : OWL_ERR_HIP;
+}
+
+owl_status owl_debug_set_timeline(long long *buffer, int64_t n_workgroups)
+{
+    if (buffer && n_workgroups < 1) return OWL_ERR_INVALID_ARG;
+    set_timeline_hook(buffer, buffer ? (long long)n_workgroups : 0);
+    return OWL_OK;
+}
+
+}  // extern "C"

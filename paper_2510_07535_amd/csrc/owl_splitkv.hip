@@ -123,20 +123,6 @@ __device__ __forceinline__ uint2 lds_read_tr16(const unsigned char *p)
     return __builtin_bit_cast(uint2, v);
 }
 
-// max over the four lanes {l, l^16, l^32, l^48}.  permlane32_swap(a, b) trades
-// a's upper 32 lanes against b's lower 32; permlane16_swap trades a's odd
-// 16-lane rows against b's even rows; fed with two copies of x, the two
-// results together hold x and its partner for every lane.
-__device__ __forceinline__ float quad_column_max(float v)
-{
-    const uint32_t x = __builtin_bit_cast(uint32_t, v);
-    auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
-    const float a = fmaxf(__builtin_bit_cast(float, (uint32_t)r[0]), __builtin_bit_cast(float, (uint32_t)r[1]));
-    const uint32_t y = __builtin_bit_cast(uint32_t, a);
-    auto r2 = __builtin_amdgcn_permlane16_swap(y, y, false, false);
-    return fmaxf(__builtin_bit_cast(float, (uint32_t)r2[0]), __builtin_bit_cast(float, (uint32_t)r2[1]));
-}
-
 // f(integral_constant<int, B>) ... f(integral_constant<int, E-1>), unrolled at compile time.
 template <int B, int E, typename F>
 __device__ __forceinline__ void static_for(F &&f)
@@ -172,7 +158,7 @@ struct Geo {
                   "cross-wave merge buffer must fit in the stage ring");
 };
 
-template <typename T, int D, int TPW, int WR, int WK>
+template <typename T, int D, int TPW, int WR, int WK, bool TL>
 __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
 {
     using GEO = Geo<T, D, TPW, WR, WK>;
@@ -204,9 +190,10 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     const int g = blockIdx.x % p.Hkv, rg = blockIdx.x / p.Hkv;
     int b = blockIdx.z;
 
-    // optional timeline of this workgroup (profiling aid)
+    // timeline of this workgroup (profiling instantiations only; the production kernels
+    // carry neither the pointer nor a branch)
     long long *tl = nullptr;
-    if (p.timeline) {
+    if constexpr (TL) {
         const long long flat = blockIdx.x + (long long)gridDim.x * (blockIdx.y + (long long)gridDim.y * blockIdx.z);
         tl = p.timeline + 10 * flat;
         if (tid == 0) {
@@ -218,10 +205,12 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
         }
     }
     auto stamp = [&](int k) {
-        if (tl && tid == 0) {
-            tl[k] = wall_clock64();
-            if (k == 2) tl[8] = clock64();            // shader cycles at both ends of the fast loop:
-            if (k == 3) tl[9] = clock64();            // their rate is the clock the chip really ran at
+        if constexpr (TL) {
+            if (tid == 0) {
+                tl[k] = wall_clock64();
+                if (k == 2) tl[8] = clock64();        // shader cycles at both ends of the fast loop:
+                if (k == 3) tl[9] = clock64();        // their rate is the clock the chip really ran at
+            }
         }
     };
 
@@ -802,9 +791,9 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
             for (int s = 0; s < n_fast; ++s) {
                 if constexpr (WK == 1) {
                     if (s > 0) {
-                        if (!late) fast_pv(pf, vf, ntag);        // early waves finish stage s-1 first
+                        if (!late) fast_pv(pf, vf, ntag);       // early waves finish stage s-1 first
                         admit(s);
-                        if (late) fast_pv(pf, vf, ntag);         // late waves carry it over
+                        if (late) fast_pv(pf, vf, ntag);        // late waves carry it over
                     }
                     fast_sx(kptr(s, 0), kptr(s, 0) + VREG, pf, vf, ntag, gtag);
                     fast_pv(pf, vf, ntag);
@@ -1041,58 +1030,47 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
             }
         }
     }
-    if (tl) {
+    if constexpr (TL) {
         __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): the partial stores have left
         stamp(5);
     }
 }
 
 // ---------------------------------------------------------------------------
-// A one-wavefront check of quad_column_max's lane semantics (test hook).
-// ---------------------------------------------------------------------------
-__global__ void __launch_bounds__(64) quad_max_kernel(const float *in, float *out)
-{
-    out[threadIdx.x] = quad_column_max(in[threadIdx.x]);
-}
-
-hipError_t launch_quad_max(const float *in, float *out, hipStream_t s)
-{
-    hipLaunchKernelGGL(quad_max_kernel, dim3(1), dim3(64), 0, s, in, out);
-    return hipGetLastError();
-}
-
-// ---------------------------------------------------------------------------
 // instantiations
 // ---------------------------------------------------------------------------
-template <typename T, int D, int TPW, int WR, int WK>
+template <typename T, int D, int TPW, int WR, int WK, bool TL>
 static void launch_variant(const KParams &p, dim3 grid, hipStream_t s)
 {
     using GEO = Geo<T, D, TPW, WR, WK>;
-    hipLaunchKernelGGL((splitkv_kernel<T, D, TPW, WR, WK>), grid, dim3(kThreads), GEO::LDS, s, p);
+    hipLaunchKernelGGL((splitkv_kernel<T, D, TPW, WR, WK, TL>), grid, dim3(kThreads), GEO::LDS, s, p);
 }
 
-#define OWL_VARIANT(DT, T, D, TPW, WR, WK)                                              \
-    Variant { DT, D, TPW, WR, WK, Geo<T, D, TPW, WR, WK>::LDS,                         \
-              &launch_variant<T, D, TPW, WR, WK>,                                       \
-              reinterpret_cast<const void *>(&splitkv_kernel<T, D, TPW, WR, WK>) }
+#define OWL_VARIANT(DT, T, D, TPW, WR, WK, TL)                                          \
+    Variant { DT, D, TPW, WR, WK, TL, Geo<T, D, TPW, WR, WK>::LDS,                     \
+              &launch_variant<T, D, TPW, WR, WK, TL>,                                   \
+              reinterpret_cast<const void *>(&splitkv_kernel<T, D, TPW, WR, WK, TL>) }
 
-#define OWL_VARIANTS_16BIT(DT, T, D)                                                    \
-    OWL_VARIANT(DT, T, D, 1, 4, 2), OWL_VARIANT(DT, T, D, 1, 8, 1),                     \
-    OWL_VARIANT(DT, T, D, 2, 8, 1), OWL_VARIANT(DT, T, D, 3, 8, 1)
+#define OWL_VARIANTS_16BIT(DT, T, D, TL)                                                \
+    OWL_VARIANT(DT, T, D, 1, 4, 2, TL), OWL_VARIANT(DT, T, D, 1, 8, 1, TL),             \
+    OWL_VARIANT(DT, T, D, 2, 8, 1, TL), OWL_VARIANT(DT, T, D, 3, 8, 1, TL)
 
 static const Variant kVariants[] = {
-    OWL_VARIANTS_16BIT(OWL_BF16, __bf16, 128),
-    OWL_VARIANTS_16BIT(OWL_BF16, __bf16, 64),
-    OWL_VARIANTS_16BIT(OWL_F16, _Float16, 128),
-    OWL_VARIANTS_16BIT(OWL_F16, _Float16, 64),
-    OWL_VARIANT(OWL_F32, float, 64, 1, 8, 1),
-    OWL_VARIANT(OWL_F32, float, 128, 1, 8, 1),
+    OWL_VARIANTS_16BIT(OWL_BF16, __bf16, 128, false),
+    OWL_VARIANTS_16BIT(OWL_BF16, __bf16, 64, false),
+    OWL_VARIANTS_16BIT(OWL_F16, _Float16, 128, false),
+    OWL_VARIANTS_16BIT(OWL_F16, _Float16, 64, false),
+    OWL_VARIANT(OWL_F32, float, 64, 1, 8, 1, false),
+    OWL_VARIANT(OWL_F32, float, 128, 1, 8, 1, false),
+    // copies with the per-workgroup timeline hook: the benchmark's type and head size only
+    OWL_VARIANTS_16BIT(OWL_BF16, __bf16, 128, true),
 };
 
-const Variant *find_variant(int dtype, int D, int tpw, int wr, int wk)
+const Variant *find_variant(int dtype, int D, int tpw, int wr, int wk, bool timeline)
 {
     for (const Variant &v : kVariants)
-        if (v.dtype == dtype && v.D == D && v.tpw == tpw && v.wr == wr && v.wk == wk) return &v;
+        if (v.dtype == dtype && v.D == D && v.tpw == tpw && v.wr == wr && v.wk == wk && v.timeline == timeline)
+            return &v;
     return nullptr;
 }
 

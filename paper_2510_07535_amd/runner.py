@@ -21,7 +21,7 @@ def _to_dev(a: np.ndarray, device) -> torch.Tensor:
 
 class VerifyStep:
     def __init__(self, case: W.Case, device: str = "cuda:0", split_tokens: int = 0,
-                 max_ctx_len: Optional[int] = None):
+                 max_ctx_len: Optional[int] = None, out_dtype: int = B.OWL_F32):
         self.case = case
         self.device = torch.device(device)
         self.q = _to_dev(case.q, self.device)
@@ -30,7 +30,8 @@ class VerifyStep:
         self.page_table = None if case.page_table is None else _to_dev(case.page_table, self.device)
         self.ctx_lens = _to_dev(case.ctx_lens, self.device)
         self.tree_parent = _to_dev(np.ascontiguousarray(case.tree_parent), self.device)
-        self.out = torch.empty((case.B, case.N, case.Hq, case.D), dtype=torch.float32, device=self.device)
+        self.out = torch.empty((case.B, case.N, case.Hq, case.D), device=self.device,
+                               dtype=torch.float32 if out_dtype == B.OWL_F32 else torch.int16)
         self.status = torch.zeros(1, dtype=torch.int32, device=self.device)
         self.desc = B.make_desc(
             batch=case.B, n_draft=case.N, n_q_heads=case.Hq, n_kv_heads=case.Hkv, head_dim=case.D,
@@ -38,7 +39,7 @@ class VerifyStep:
             max_ctx_len=case.max_ctx_len if max_ctx_len is None else max_ctx_len,
             qkv_dtype=case.dtype, scale=case.scale, kv_stride_page=case.stride_page,
             kv_stride_head=case.stride_head, kv_stride_token=case.stride_token,
-            n_pool_pages=case.n_pool_pages, split_tokens=split_tokens)
+            n_pool_pages=case.n_pool_pages, split_tokens=split_tokens, out_dtype=out_dtype)
         self.plan = B.owl_verify_attn_plan(self.desc)
         self.workspace = torch.empty(max(self.plan.workspace_bytes, 256), dtype=torch.uint8,
                                      device=self.device)
@@ -58,8 +59,10 @@ class VerifyStep:
         return self.out
 
     def result(self) -> np.ndarray:
+        """``out`` on the host: float32, or the uint16 bit patterns of a 16-bit output type."""
         torch.cuda.synchronize(self.device)
-        return self.out.cpu().numpy()
+        a = self.out.cpu().numpy()
+        return a if a.dtype == np.float32 else a.view(np.uint16)
 
     def dev_status(self) -> int:
         torch.cuda.synchronize(self.device)

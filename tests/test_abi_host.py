@@ -21,19 +21,21 @@ def _good(**over):
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "owl.h")).read()
-    declared = set(re.findall(r"\b(owl_[a-z_]+)\s*\(", header))
-    assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
     lib = B.lib()
-    for name in declared:
-        assert getattr(lib, name) is not None
+    for fname, names in (("owl.h", B.EXPORTS), ("owl_probe.h", B.PROBE_EXPORTS)):
+        header = open(os.path.join(ROOT, "include", fname)).read()
+        declared = set(re.findall(r"\b(owl_[a-z_]+)\s*\(", header))
+        assert declared == set(names), (fname, declared ^ set(names))
+        for name in declared:
+            assert getattr(lib, name) is not None
     assert lib.owl_version().decode().count(".") == 1
 
 
 def test_struct_layout_matches_header():
-    assert ctypes.sizeof(B.VerifyDesc) == 12 * 4 + 4 * 8
-    assert B.VerifyDesc.kv_stride_page.offset == 48
-    assert ctypes.sizeof(B.Plan) == 8 * 4 + 8
+    assert ctypes.sizeof(B.VerifyDesc) == 12 * 4 + 4 * 8 + 2 * 4
+    assert B.VerifyDesc.out_dtype.offset == 44 and B.VerifyDesc.kv_stride_page.offset == 48
+    assert B.VerifyDesc.flags.offset == 80
+    assert ctypes.sizeof(B.Plan) == 10 * 4 + 8 and B.Plan.workspace_bytes.offset == 40
 
 
 def test_plan_matches_shapes():
@@ -236,3 +238,32 @@ def test_drafter_alpha_host():
     assert B.owl_drafter_alpha(1, 8) == pytest.approx(2 * math.sqrt(2) / 8, rel=1e-6)
     with pytest.raises(B.OwlError):
         B.owl_drafter_alpha(0, 8)
+
+
+def test_output_type_and_reserved_fields():
+    for over, code in ((dict(out_dtype=7), B.OWL_ERR_UNSUPPORTED), (dict(flags=1), B.OWL_ERR_INVALID_ARG)):
+        with pytest.raises(B.OwlError) as e:
+            B.owl_verify_attn_plan(_good(**over))
+        assert e.value.code == code
+    for od in (B.OWL_F32, B.OWL_BF16, B.OWL_F16):
+        B.owl_verify_attn_plan(_good(out_dtype=od))
+
+
+def test_init_and_noalloc_reject_before_touching_a_device():
+    lib = B.lib()
+    A = 0x10000
+    assert lib.owl_verify_attn_init(None) == B.OWL_ERR_INVALID_ARG
+    assert lib.owl_verify_attn_init(ctypes.byref(_good(head_dim=96))) == B.OWL_ERR_UNSUPPORTED
+    # the entry point without a workspace: a shape whose partials exceed the library's fixed buffer
+    big = _good(batch=16, n_draft=26, max_ctx_len=65536, max_pages_per_seq=4100, n_pool_pages=16 * 4100)
+    assert B.owl_verify_attn_workspace_size(big) > B.OWL_NOALLOC_SCRATCH_BYTES
+    assert lib.owl_verify_attn_noalloc(ctypes.byref(big), A, A, A, A, A, A, A, None, None) == B.OWL_ERR_WORKSPACE
+    assert lib.owl_verify_attn_noalloc(None, A, A, A, A, A, A, A, None, None) == B.OWL_ERR_INVALID_ARG
+    header = open(os.path.join(ROOT, "include", "owl.h")).read()
+    assert f"#define OWL_NOALLOC_SCRATCH_BYTES ({B.OWL_NOALLOC_SCRATCH_BYTES >> 20}u << 20)" in header
+
+
+def test_timeline_switch_checks_its_arguments():
+    lib = B.lib()
+    assert lib.owl_debug_set_timeline(0x10000, 0) == B.OWL_ERR_INVALID_ARG
+    assert lib.owl_debug_set_timeline(None, 0) == B.OWL_OK

@@ -86,6 +86,28 @@ def test_small_shapes_match_oracle(oracle_mod, case):
 
 
 # ---------------------------------------------------------------------------
+# 16-bit output types
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("N,G", [(6, 4), (26, 4)])
+def test_sixteen_bit_outputs_are_the_rounded_fp32_result(oracle_mod, N, G):
+    """out_dtype = bf16 / f16: bit for bit the fp32 output rounded to nearest even, and within the
+    fp32 bar widened by one unit in the last place of the output type against the rounded oracle."""
+    r = _rng(640 + N)
+    case = W.make_case("out16", 640 + N, dtype=W.DT_BF16, Hq=2 * G, Hkv=2, D=128, ctx_lens=[3000, 500],
+                       trees=[W.random_tree(N, 5, r) for _ in range(2)])
+    ref, _ = _run(case)
+    want64 = oracle_mod.verify_attn_case(case)
+    for od, dt in ((B.OWL_BF16, W.DT_BF16), (B.OWL_F16, W.DT_F16)):
+        got, step = _run(case, out_dtype=od)
+        assert got.dtype == np.uint16
+        assert np.array_equal(got, W.store(ref, dt)), od
+        want = W.widen(W.store(want64.astype(np.float32), dt), dt)           # the oracle rounded to the output type
+        ulp = np.abs(want) * (2.0 ** -8 if dt == W.DT_BF16 else 2.0 ** -11) + 1e-7
+        err = np.abs(W.widen(got, dt) - want)
+        assert (err <= 1e-2 + ulp).all() and err.mean() <= 1e-3 + ulp.mean(), (od, err.max())
+
+
+# ---------------------------------------------------------------------------
 # the five named configurations
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("idx", range(5), ids=W.CONFIG_NAMES)
@@ -473,7 +495,7 @@ def test_graph_capture_replays_match_eager(oracle_mod):
     case = W.make_case("graph", 61, dtype=W.DT_BF16, Hq=16, Hkv=4, D=128, ctx_lens=ctx,
                        trees=[W.random_tree(12, 4, r) for _ in ctx])
     step = VerifyStep(case)
-    step.run()                                            # warm-up outside the capture (one-time kernel attributes)
+    B.owl_verify_attn_init(step.desc)                     # one-time kernel attributes, outside the capture
     torch.cuda.synchronize()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
