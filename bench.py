@@ -63,6 +63,9 @@ def parse():
     ap.add_argument("--all", action="store_true",
                     help="also time the steps around the attention and the drafter cell ('step_kernels', 'drafter_cell')")
     ap.add_argument("--no-others", action="store_true", help="time only the --config workload (no 'others')")
+    ap.add_argument("--settle-ms", type=float, default=400.0,
+                    help="milliseconds of the same step run before the warm-up steps, so that the clock governor has "
+                         "reached its steady state under this load when the timed region starts (0 = none)")
     ap.add_argument("--split-tokens", type=int, default=0, help="override the library's split size (tuning)")
     ap.add_argument("--dtype", choices=("bf16", "f16"), default="bf16",
                     help="storage type of q/K/V (the configurations list bf16; f16 is the paper's type)")
@@ -70,6 +73,10 @@ def parse():
                     help="also time the drafter's recurrent cell (reported under 'drafter_cell'; implied by --all)")
     ap.add_argument("--draft-sweep", action="store_true",
                     help="also time a 64K-context step for 1..60 drafted tokens (reported under 'draft_count_sweep')")
+    ap.add_argument("--evidence", action="store_true",
+                    help="also run the experiments the design notes lean on (reported under 'evidence'): the same "
+                         "launches on all-zero operands, shader cycles against duration over a series of launches, the "
+                         "step probe of the matrix pipe, the cost of an empty event bracket")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
     return ap.parse_args()
@@ -109,7 +116,18 @@ class Rotating:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
-    def time_steps_with_kernel(self, steps, warmup):
+    def settle(self, ms):
+        """Runs the step for about `ms` milliseconds (untimed): a verify step never meets an idle chip
+        in use, and the power management takes some hundred milliseconds of load to settle."""
+        if ms <= 0:
+            return
+        t_end = time.perf_counter() + ms * 1e-3
+        while time.perf_counter() < t_end:
+            for _ in range(16):
+                self.run()
+            self.torch.cuda.synchronize()
+
+    def time_steps_with_kernel(self, steps, warmup, settle_ms=0.0):
         """The timed region (wall clock over exactly `steps` steps) with the split-KV kernel of every
         fourth step bracketed by HIP events on the launch stream (such a step is enqueued as its two
         phases: the same kernels), then two sampling passes outside it: more bracketed kernels until
@@ -119,6 +137,7 @@ class Rotating:
         every = 4
         new_pair = lambda: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
         ev = [new_pair() for _ in range((steps + every - 1) // every)]
+        self.settle(settle_ms)
         for _ in range(warmup):
             self.run()
         torch.cuda.synchronize()
@@ -220,6 +239,100 @@ def kernel_shader_clock(rot):
         return None
     import numpy as np
     return float(np.median((t[:, 9] - t[:, 8]) / ((t[:, 3] - t[:, 2]) * 10.0)))
+
+
+def evidence(rot, case):
+    """Experiments behind the statements on what bounds the tree shapes (design notes, kernel section)."""
+    import numpy as np
+    import torch
+    from paper_2510_07535_amd import binding as B
+    out = {}
+    # (1) an empty event bracket: what HIP events add to a bracketed kernel
+    rot.settle(200)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(32)]
+    for a, b in pairs:
+        rot.run()
+        a.record()
+        b.record()
+    torch.cuda.synchronize()
+    out["empty_event_bracket_us"] = float(np.median([a.elapsed_time(b) * 1e3 for a, b in pairs]))
+    # (2) shader cycles of the main loop against the duration of the launch, over a series of launches
+    nwg = rot.step.plan.n_workgroups
+    n = 120
+    bufs = [torch.zeros(10 * nwg, dtype=torch.int64, device="cuda") for _ in range(n)]
+    evs = []
+    try:
+        for i in range(n):
+            B.owl_debug_set_timeline(bufs[i])
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            rot.run(phases=1)
+            b.record()
+            rot.run(phases=2)
+            evs.append((a, b))
+    finally:
+        B.owl_debug_set_timeline(None)
+    torch.cuda.synchronize()
+    cyc, clk, us, span, phases = [], [], [], [], []
+    for i in range(n):
+        t = bufs[i].cpu().numpy().reshape(nwg, 10)
+        t = t[t[:, 0] > 0]
+        if len(t) == 0:
+            continue
+        rel = (t[:, :6] - t[:, 0].min()) * 0.01
+        phases.append(np.median(rel[:, 1:] - rel[:, :-1], axis=0))
+        span.append(float(rel[:, 5].max()))
+        tt = t[(t[:, 3] - t[:, 2]) >= 100]
+        cyc.append(float(np.median(tt[:, 9] - tt[:, 8])))
+        clk.append(float(np.median((tt[:, 9] - tt[:, 8]) / ((tt[:, 3] - tt[:, 2]) * 10.0))))
+        us.append(evs[i][0].elapsed_time(evs[i][1]) * 1e3)
+    if cyc:
+        ph = np.median(np.array(phases), axis=0)
+        out["launch_series"] = {
+            "launches": len(cyc), "workgroups": int(nwg),
+            "main_loop_cycles": {"min": min(cyc), "median": float(np.median(cyc)), "max": max(cyc)},
+            "shader_clock_GHz": {"min": min(clk), "median": float(np.median(clk)), "max": max(clk)},
+            "event_us": {"min": min(us), "median": float(np.median(us)), "max": max(us)},
+            "device_span_us": {"min": min(span), "median": float(np.median(span)), "max": max(span),
+                               "what": "first workgroup's entry to last workgroup's exit on the device's 100 MHz clock"},
+            "corr_clock_vs_event_us": float(np.corrcoef(clk, us)[0, 1]) if len(cyc) > 2 else None,
+            "corr_cycles_vs_event_us": float(np.corrcoef(cyc, us)[0, 1]) if len(cyc) > 2 else None,
+            "phase_medians_us": {"set-up": float(ph[0]), "first stage in LDS": float(ph[1]), "fast loop": float(ph[2]),
+                                 "careful tail": float(ph[3]), "epilogue": float(ph[4])},
+        }
+    del bufs
+    # (3) the same launches on all-zero operands: same instructions, same traffic, less switching
+    real = rot.time_steps_with_kernel(60, 10, 200)
+    saved = [(k.clone(), v.clone()) for k, v in rot.pools[:1]]
+    q_saved = rot.step.q.clone()
+    for k, v in rot.pools:
+        k.zero_()
+        v.zero_()
+    rot.step.q.zero_()
+    zero = rot.time_steps_with_kernel(60, 10, 200)
+    rot.step.q.copy_(q_saved)
+    for (k, v) in rot.pools:
+        k.copy_(saved[0][0])
+        v.copy_(saved[0][1])
+    out["zero_operands"] = {"kernel_us_random_data": real["kernel_avg"] * 1e6, "kernel_us_all_zero_data": zero["kernel_avg"] * 1e6,
+                            "step_us_random_data": real["step"] * 1e6, "step_us_all_zero_data": zero["step"] * 1e6}
+    del saved
+    # (4) the step probe: how busy two wavefronts per SIMD keep the matrix pipe on the loop's instruction mix
+    src = torch.randn(8192, device="cuda").to(torch.bfloat16)
+    sink = torch.zeros(256 * 512, dtype=torch.float32, device="cuda")
+    cycles = torch.zeros(256 * 8, dtype=torch.int64, device="cuda")
+    iters = 4000
+    rows = []
+    for variant, name, tiles in B.STEP_PROBE_VARIANTS:
+        for _ in range(2):
+            B.owl_step_probe(variant, src, iters, sink, cycles, 256)
+        torch.cuda.synchronize()
+        per = float(cycles.double().mean().item()) / iters
+        need = tiles * 17 * 16.0
+        rows.append({"variant": name, "cycles_per_step_and_simd": per, "matrix_pipe_cycles_needed": need,
+                     "matrix_pipe_busy": need / per})
+    out["step_probe"] = rows
+    return out
 
 
 def cpu_baseline(case, budget_rows=None):
@@ -421,7 +534,7 @@ def bench_config(idx, args):
     from paper_2510_07535_amd import workloads as W
     case = W.make_config(idx, dtype={"bf16": W.DT_BF16, "f16": W.DT_F16}[args.dtype])
     rot = Rotating(case, split_tokens=args.split_tokens)
-    t = rot.time_steps_with_kernel(args.steps, args.warmup)
+    t = rot.time_steps_with_kernel(args.steps, args.warmup, args.settle_ms)
     sec = t["step"]
     res = {
         "workload": W.CONFIG_NAMES[idx], "config_index": idx,
@@ -482,6 +595,8 @@ def main():
         rl["frac_of_measured_ceiling"] = floor / ksec
         rl["measured_ceiling"] = ("the longer of: algorithmic bytes / streaming-read probe rate, algorithmic flop / "
                                   "matrix-pipe probe rate on random operands, both from this run")
+    if args.evidence:
+        line["evidence"] = evidence(rot, case)
     if not args.no_others:
         others = []
         for idx in (1, 2, 3, 4):

@@ -52,6 +52,32 @@ owl_status owl_gather_read_probe(const void *src, const int32_t *block_order, in
                                  uint32_t *sink, int32_t n_workgroups, void *stream);
 
 /*
+ * The instruction mix of one 32-key step of the split-KV fast loop (K fragments
+ * from LDS, QK^T MFMAs, exp2 softmax, conversion, V fragments from LDS, PV and
+ * row-sum MFMAs: 17 MFMAs of 16x16x32 per 16-row tile) on LDS- and
+ * register-resident data, no HBM traffic: n_workgroups workgroups of 8 wavefronts
+ * run `iters` (even, >= 2) steps; wavefronts 0..3 hold TA row tiles, 4..7 TB
+ * (one of each per SIMD).  The variants differ in what the real loop adds:
+ *     OWL_STEP_PROBE_3_2              3 + 2 tiles, nothing else
+ *     OWL_STEP_PROBE_3_2_BARRIER      + a workgroup barrier every 64 keys
+ *     OWL_STEP_PROBE_3_2_V64          + V fragments by 64-bit LDS reads
+ *     OWL_STEP_PROBE_3_2_BARRIER_V64  + both (the real three-tile loop's structure)
+ *     OWL_STEP_PROBE_2_2 / _2_2_BARRIER_V64   the same with 2 + 2 tiles
+ * src: 16 KiB of bf16 operand values (device, 16-byte aligned); sink:
+ * n_workgroups * 512 floats; cycles: n_workgroups * 8 int64, the shader cycles of
+ * each wavefront's loop.  With T = TA + TB tiles per SIMD the matrix pipe needs
+ * T * 17 * 16 cycles per step, so its busy fraction is that over cycles / iters.
+ */
+#define OWL_STEP_PROBE_3_2 0
+#define OWL_STEP_PROBE_3_2_BARRIER 1
+#define OWL_STEP_PROBE_3_2_V64 2
+#define OWL_STEP_PROBE_3_2_BARRIER_V64 3
+#define OWL_STEP_PROBE_2_2 4
+#define OWL_STEP_PROBE_2_2_BARRIER_V64 5
+owl_status owl_step_probe(int32_t variant, const void *src, int32_t iters, float *sink, long long *cycles,
+                          int32_t n_workgroups, void *stream);
+
+/*
  * Self-test of the cross-lane step of the in-kernel softmax: one wavefront
  * reads in64[64] and writes, for every lane l, the maximum over the lanes
  * {l, l^16, l^32, l^48} (the four lanes that hold the keys of one query row in

@@ -37,7 +37,7 @@ EXPORTS = (
 # ... and in include/owl_probe.h (measurement and self-test aids)
 PROBE_EXPORTS = (
     "owl_stream_read_probe", "owl_gather_read_probe", "owl_mfma_probe", "owl_selftest_quad_max",
-    "owl_debug_set_timeline",
+    "owl_debug_set_timeline", "owl_step_probe",
 )
 OWL_NOALLOC_SCRATCH_BYTES = 48 << 20
 
@@ -127,6 +127,8 @@ def lib() -> ctypes.CDLL:
         l.owl_gather_read_probe.argtypes = [vp, vp, i32, vp, i32, vp]
         l.owl_debug_set_timeline.restype = ctypes.c_int
         l.owl_debug_set_timeline.argtypes = [vp, i64]
+        l.owl_step_probe.restype = ctypes.c_int
+        l.owl_step_probe.argtypes = [i32, vp, i32, vp, vp, i32, vp]
         l.owl_selftest_quad_max.restype = ctypes.c_int
         l.owl_selftest_quad_max.argtypes = [vp, vp, vp]
         l.owl_build_tree_mask.restype = ctypes.c_int
@@ -258,6 +260,18 @@ def owl_debug_set_timeline(buffer) -> None:
     number of workgroups it has room for), or None to switch the recording off."""
     n = 0 if buffer is None else int(buffer.numel()) // 10
     _check(lib().owl_debug_set_timeline(_ptr(buffer), n), "owl_debug_set_timeline")
+
+
+STEP_PROBE_VARIANTS = (
+    (0, "3 + 2 tiles", 5), (1, "3 + 2 tiles, barrier every 64 keys", 5), (2, "3 + 2 tiles, V by 64-bit LDS reads", 5),
+    (3, "3 + 2 tiles, barrier + 64-bit V reads", 5), (4, "2 + 2 tiles", 4), (5, "2 + 2 tiles, barrier + 64-bit V reads", 4),
+)
+
+
+def owl_step_probe(variant: int, src, iters: int, sink, cycles, n_workgroups: int, stream: Optional[int] = None) -> None:
+    rc = lib().owl_step_probe(variant, _ptr(src), iters, _ptr(sink), _ptr(cycles), n_workgroups,
+                              _stream() if stream is None else stream)
+    _check(rc, "owl_step_probe")
 
 
 def owl_selftest_quad_max(in64, out64, stream: Optional[int] = None) -> None:

@@ -116,6 +116,116 @@ __global__ void __launch_bounds__(512) mfma_probe_kernel(const uint4 *src, int n
     if (clock_ghz && threadIdx.x == 0) clock_ghz[blockIdx.x] = w1 > w0 ? (float)(c1 - c0) / ((float)(w1 - w0) * 10.0f) : 0.f;
 }
 
+// ---------------------------------------------------------------------------
+// Step probe: the instruction mix of one 32-key step of the split-KV fast loop
+// (K fragments from LDS, QK MFMAs, exp2 softmax, pack, V fragments from LDS, PV
+// and row-sum MFMAs) on register- and LDS-resident data, without the HBM side:
+// what the matrix pipe can be kept busy at by two wavefronts per SIMD holding
+// TA and TB row tiles, with and without a workgroup barrier every 64 keys, with
+// the V fragments fetched by 128-bit or by 64-bit LDS reads.  Plain step
+// structure, scheduled by the compiler.  Every wavefront reports the shader
+// cycles of its loop.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ probe_f32x4 probe_mfma(uint4 a, uint4 b, probe_f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(probe_bf16x8, a),
+                                                   __builtin_bit_cast(probe_bf16x8, b), c, 0, 0, 0);
+}
+
+__device__ __forceinline__ uint32_t probe_pack2(float a, float b)
+{
+    typedef float p_f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 p_bf16x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(p_f32x2{a, b}, p_bf16x2));
+}
+
+template <int T, bool BAR, bool V64>
+__device__ __forceinline__ void step_probe_wave(const unsigned char *lds, int iters, const uint4 *qsrc, float *out,
+                                                long long *cyc)
+{
+    const int lane = threadIdx.x & 63;
+    uint4 qf[T][4];
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) qf[t][k] = qsrc[(lane + 64 * (t * 4 + k)) & 1023];
+    probe_f32x4 O[T][9];
+    float m[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        m[t] = 3.0f + t;
+#pragma unroll
+        for (int u = 0; u < 9; ++u) O[t][u] = probe_f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
+    const long long c0 = clock64();
+    for (int it = 0; it < iters; ++it) {
+        const unsigned char *Kb = lds + (it & 1) * 8192 + lane * 16;
+        uint4 kf[2][4];
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) kf[kt][kk] = *reinterpret_cast<const uint4 *>(Kb + (kt * 4 + kk) * 1024);
+        uint4 pf[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            probe_f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                s0 = probe_mfma(kf[0][kk], qf[t][kk], s0);
+                s1 = probe_mfma(kf[1][kk], qf[t][kk], s1);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                s0[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[r], 0.127f, -m[t]));
+                s1[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[r], 0.127f, -m[t]));
+            }
+            pf[t] = make_uint4(probe_pack2(s0[0], s0[1]), probe_pack2(s0[2], s0[3]), probe_pack2(s1[0], s1[1]),
+                               probe_pack2(s1[2], s1[3]));
+        }
+        uint4 vf[8];
+        if constexpr (V64) {
+            const unsigned char *Vh = lds + 16384 + (it & 1) * 8192 + lane * 8;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const uint2 lo = *reinterpret_cast<const uint2 *>(Vh + u * 1024);
+                const uint2 hi = *reinterpret_cast<const uint2 *>(Vh + u * 1024 + 512);
+                vf[u] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+            }
+        } else {
+            const unsigned char *Vb = lds + 16384 + (it & 1) * 8192 + lane * 16;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) vf[u] = *reinterpret_cast<const uint4 *>(Vb + u * 1024);
+        }
+        if constexpr (BAR)
+            if (it & 1) __syncthreads();              // every wavefront of the workgroup runs the same number of steps
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int t = 0; t < T; ++t) O[t][u] = probe_mfma(vf[u], pf[t], O[t][u]);
+#pragma unroll
+        for (int t = 0; t < T; ++t) O[t][8] = probe_mfma(ones, pf[t], O[t][8]);
+    }
+    const long long c1 = clock64();
+    float s = 0.f;
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int u = 0; u < 9; ++u) s += O[t][u][0] + O[t][u][3];
+    out[blockIdx.x * 512 + threadIdx.x] = s;
+    if (lane == 0) cyc[blockIdx.x * 8 + (threadIdx.x >> 6)] = c1 - c0;
+}
+
+template <bool BAR, bool V64, int TA, int TB>
+__global__ void __launch_bounds__(512) step_probe_kernel(const uint4 *src, int iters, float *out, long long *cyc)
+{
+    __shared__ unsigned char lds[32768];
+    for (int i = threadIdx.x; i < 2048; i += 512) reinterpret_cast<uint4 *>(lds)[i] = src[i & 1023];
+    __syncthreads();
+    if (threadIdx.x < 256) step_probe_wave<TA, BAR, V64>(lds, iters, src, out, cyc);
+    else step_probe_wave<TB, BAR, V64>(lds, iters, src, out, cyc);
+}
+
 // One wavefront: out[l] = max over the lanes {l, l^16, l^32, l^48} of in[.].
 __global__ void __launch_bounds__(64) quad_max_kernel(const float *in, float *out)
 {
@@ -187,6 +297,26 @@ owl_status owl_selftest_quad_max(const float *in64, float *out64, void *stream)
 {
     if (!in64 || !out64) return OWL_ERR_INVALID_ARG;
     hipLaunchKernelGGL(quad_max_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), in64, out64);
+    return hipGetLastError() == hipSuccess ? OWL_OK : OWL_ERR_HIP;
+}
+
+owl_status owl_step_probe(int32_t variant, const void *src, int32_t iters, float *sink, long long *cycles,
+                          int32_t n_workgroups, void *stream)
+{
+    if (!src || !sink || !cycles || iters < 2 || iters % 2 != 0 || n_workgroups < 1 || misaligned16(src))
+        return OWL_ERR_INVALID_ARG;
+    const dim3 grid(n_workgroups), block(512);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint4 *s4 = static_cast<const uint4 *>(src);
+    switch (variant) {
+    case OWL_STEP_PROBE_3_2: hipLaunchKernelGGL((step_probe_kernel<false, false, 3, 2>), grid, block, 0, st, s4, iters, sink, cycles); break;
+    case OWL_STEP_PROBE_3_2_BARRIER: hipLaunchKernelGGL((step_probe_kernel<true, false, 3, 2>), grid, block, 0, st, s4, iters, sink, cycles); break;
+    case OWL_STEP_PROBE_3_2_V64: hipLaunchKernelGGL((step_probe_kernel<false, true, 3, 2>), grid, block, 0, st, s4, iters, sink, cycles); break;
+    case OWL_STEP_PROBE_3_2_BARRIER_V64: hipLaunchKernelGGL((step_probe_kernel<true, true, 3, 2>), grid, block, 0, st, s4, iters, sink, cycles); break;
+    case OWL_STEP_PROBE_2_2: hipLaunchKernelGGL((step_probe_kernel<false, false, 2, 2>), grid, block, 0, st, s4, iters, sink, cycles); break;
+    case OWL_STEP_PROBE_2_2_BARRIER_V64: hipLaunchKernelGGL((step_probe_kernel<true, true, 2, 2>), grid, block, 0, st, s4, iters, sink, cycles); break;
+    default: return OWL_ERR_INVALID_ARG;
+    }
     return hipGetLastError() == hipSuccess ? OWL_OK : OWL_ERR_HIP;
 }
 
