@@ -318,21 +318,42 @@ def evidence(rot, case):
                             "step_us_random_data": real["step"] * 1e6, "step_us_all_zero_data": zero["step"] * 1e6}
     del saved
     # (4) the step probe: how busy two wavefronts per SIMD keep the matrix pipe on the loop's instruction mix
+    out["step_probe"] = step_probe_rows()
+    return out
+
+
+def step_probe_rows(variants=None, iters=4000, nwg=256):
+    """The step probe on the whole chip: cycles per 32-key step and SIMD (the matrix pipe's busy fraction
+    follows) and, from HIP events around the launch, the MFMA rate the chip sustained on that
+    instruction mix under its power limit with no HBM traffic at all."""
+    import torch
+    from paper_2510_07535_amd import binding as B
     src = torch.randn(8192, device="cuda").to(torch.bfloat16)
-    sink = torch.zeros(256 * 512, dtype=torch.float32, device="cuda")
-    cycles = torch.zeros(256 * 8, dtype=torch.int64, device="cuda")
-    iters = 4000
+    sink = torch.zeros(nwg * 512, dtype=torch.float32, device="cuda")
+    cycles = torch.zeros(nwg * 8, dtype=torch.int64, device="cuda")
     rows = []
     for variant, name, tiles in B.STEP_PROBE_VARIANTS:
-        for _ in range(2):
-            B.owl_step_probe(variant, src, iters, sink, cycles, 256)
+        if variants is not None and variant not in variants:
+            continue
+        for _ in range(3):
+            B.owl_step_probe(variant, src, iters, sink, cycles, nwg)
         torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        reps = 8
+        for _ in range(reps):
+            B.owl_step_probe(variant, src, iters, sink, cycles, nwg)
+        b.record()
+        torch.cuda.synchronize()
+        sec = a.elapsed_time(b) * 1e-3 / reps
         per = float(cycles.double().mean().item()) / iters
         need = tiles * 17 * 16.0
+        flop = nwg * 4.0 * tiles * 17 * 16384.0 * iters          # 16 of the 17 MFMAs per tile-step are algorithmic
         rows.append({"variant": name, "cycles_per_step_and_simd": per, "matrix_pipe_cycles_needed": need,
-                     "matrix_pipe_busy": need / per})
-    out["step_probe"] = rows
-    return out
+                     "matrix_pipe_busy": need / per, "TFLOPs_all_mfma": flop / sec / 1e12,
+                     "TFLOPs_algorithmic": flop * 16 / 17 / sec / 1e12,
+                     "shader_clock_GHz": per * iters / sec / 1e9})
+    return rows
 
 
 def cpu_baseline(case, budget_rows=None):
@@ -588,6 +609,11 @@ def main():
             tf, ghz = mfma_probe_tflops(kind)
             rl["mfma"][key + "_TFLOPs"] = tf
             rl["shader_clock_GHz"]["mfma_" + key] = ghz
+        # the loop's own instruction mix without the HBM side: barrier + 64-bit V reads, 3 + 2 or 2 + 2 tiles
+        sp = step_probe_rows(variants=(3,) if main_res["plan"]["tiles_per_wave"] == 3 else (5,))
+        rl["mfma"]["step_probe_TFLOPs_algorithmic"] = sp[0]["TFLOPs_algorithmic"]
+        rl["mfma"]["step_probe_variant"] = sp[0]["variant"]
+        rl["mfma"]["frac_of_step_probe"] = rl["mfma"]["achieved"] / sp[0]["TFLOPs_algorithmic"]
         # the same kernel time against what this very box sustained in the probes of this run
         ksec = rl["kernel_avg_us"] * 1e-6
         floor = max(kbytes / (rl["stream_read_probe_GBps"] * 1e9),

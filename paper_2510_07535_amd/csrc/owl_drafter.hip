@@ -115,7 +115,9 @@ __global__ void __launch_bounds__(kProjWaves * 64) drafter_proj_kernel(const uin
             const int ks = live ? ks0 + u : 0;
 #pragma unroll
             for (int nb = 0; nb < kProjTiles; ++nb) {
-                b[u][nb] = *reinterpret_cast<const d_i32x4 *>(wp[nb] + ks * w_step);
+                // every weight is used once: a non-temporal load, which leaves the caches to h (re-read by
+                // every workgroup) and is worth 11 % on this chip (square step: 206 -> 183 us)
+                b[u][nb] = __builtin_nontemporal_load(reinterpret_cast<const d_i32x4 *>(wp[nb] + ks * w_step));
                 if (!live) b[u][nb] = d_i32x4{0, 0, 0, 0};
             }
 #pragma unroll

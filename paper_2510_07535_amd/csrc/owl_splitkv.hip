@@ -89,10 +89,15 @@ __device__ __forceinline__ uint32_t ones2()
 }
 
 // 16 bytes per lane from global memory straight into LDS: lane l's data lands
-// at lds_addr + 16*l.  lds_addr must be uniform over the wavefront.
+// at lds_addr + 16*l.  lds_addr must be uniform over the wavefront.  K and V are
+// read exactly once, so the transfer is marked non-temporal (`nt`): the lines are
+// not kept in L2 or the memory-side cache, which leaves those to the queries, the
+// page lists and the partials, and makes the 32K chain step 10 % shorter (the
+// 128K tree step 2.5 %); the scope bits of the instruction make no difference.
+#define OWL_DMA_POLICY " nt"
 __device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_addr)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n"
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" OWL_DMA_POLICY "\n"
                  :
                  : "s"(lds_addr), "v"(gptr)
                  : "memory", "m0");
@@ -101,7 +106,7 @@ __device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_addr)
 // The same with a wave-uniform 64-bit base and a 32-bit per-lane byte offset.
 __device__ __forceinline__ void dma16s(uint64_t sbase, uint32_t voff, uint32_t lds_addr)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n"
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" OWL_DMA_POLICY "\n"
                  :
                  : "s"(lds_addr), "v"(voff), "s"(sbase)
                  : "memory", "m0");
