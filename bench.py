@@ -14,8 +14,8 @@ Prints ONE JSON line.  `value` is algorithmic KV bytes per second
 (sum_b (L_b + N) * Hkv * D * 2 tensors * 2 bytes, divided by the time of the
 whole step); `ms_per_step` is the verify-step time: wall clock over exactly
 --steps steps between two synchronisations.  `roofline` prices the split-KV
-kernel alone from HIP events around its launches (every fourth step of the
-timed region, plus a sampling pass after it so that there are at least 32
+kernel alone from HIP events attached to its dispatch (every fourth step of
+the timed region, plus a sampling pass after it so that there are at least 32
 samples whatever --steps is) against whichever of the two roofs bounds the
 shape: 8 TB/s of HBM over the algorithmic K/V bytes or 2.5 PFLOP/s of dense
 bf16 MFMA over the algorithmic flop; both sides are printed.  `step_us` holds
@@ -127,16 +127,24 @@ class Rotating:
                 self.run()
             self.torch.cuda.synchronize()
 
+    def run_split_timed(self, timer):
+        k, v = self.pools[self.i % len(self.pools)]
+        self.i += 1
+        self.step.run_split_timed(timer, k=k, v=v)
+
     def time_steps_with_kernel(self, steps, warmup, settle_ms=0.0):
-        """The timed region (wall clock over exactly `steps` steps) with the split-KV kernel of every
-        fourth step bracketed by HIP events on the launch stream (such a step is enqueued as its two
-        phases: the same kernels), then two sampling passes outside it: more bracketed kernels until
-        there are MIN_KERNEL_SAMPLES, and STEP_SAMPLES steps with an event after each for the
-        distribution of single-step times.  Returns a dict of seconds."""
+        """The timed region (wall clock over exactly `steps` steps).  In every fourth step the split-KV
+        kernel is launched with a pair of HIP events attached to its own dispatch (begin and end of
+        the kernel on the launch stream; such a step is enqueued as its two phases: the same
+        kernels).  Then, outside the region: more such launches until there are MIN_KERNEL_SAMPLES, a
+        few launches bracketed by ordinary event records instead (for comparison: those read ~5 us
+        more), and STEP_SAMPLES steps with an event after each for the distribution of single-step
+        times.  Returns a dict of seconds."""
         torch = self.torch
+        from paper_2510_07535_amd.binding import KernelTimer
         every = 4
-        new_pair = lambda: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-        ev = [new_pair() for _ in range((steps + every - 1) // every)]
+        timers = [KernelTimer() for _ in range(max((steps + every - 1) // every, MIN_KERNEL_SAMPLES))]
+        n_timed = (steps + every - 1) // every
         self.settle(settle_ms)
         for _ in range(warmup):
             self.run()
@@ -144,18 +152,21 @@ class Rotating:
         t0 = time.perf_counter()
         for i in range(steps):
             if i % every == 0:
-                a, b = ev[i // every]
-                a.record()
-                self.run(phases=1)
-                b.record()
+                self.run_split_timed(timers[i // every])
                 self.run(phases=2)
             else:
                 self.run()
         torch.cuda.synchronize()
         sec = (time.perf_counter() - t0) / steps
-        n_timed = len(ev)
-        extra = [new_pair() for _ in range(max(0, MIN_KERNEL_SAMPLES - n_timed))]
-        for i, (a, b) in enumerate(extra):
+        for tm in timers[n_timed:]:
+            for _ in range(every - 1):
+                self.run()
+            self.run_split_timed(tm)
+            self.run(phases=2)
+        torch.cuda.synchronize()
+        ks = sorted(tm.elapsed_ms() * 1e-3 for tm in timers)
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(16)]
+        for a, b in pairs:
             for _ in range(every - 1):
                 self.run()
             a.record()
@@ -163,7 +174,7 @@ class Rotating:
             b.record()
             self.run(phases=2)
         torch.cuda.synchronize()
-        ks = sorted(a.elapsed_time(b) * 1e-3 for a, b in ev + extra)
+        bracket = sorted(a.elapsed_time(b) * 1e-3 for a, b in pairs)
         marks = [torch.cuda.Event(enable_timing=True) for _ in range(STEP_SAMPLES + 1)]
         marks[0].record()
         for m in marks[1:]:
@@ -174,6 +185,7 @@ class Rotating:
         pct = lambda v, q: v[min(len(v) - 1, int(q * len(v)))]
         return {"step": sec, "kernel_avg": sum(ks) / len(ks), "kernel_p10": pct(ks, 0.1), "kernel_p50": pct(ks, 0.5),
                 "kernel_p90": pct(ks, 0.9), "kernel_samples": len(ks), "kernel_samples_in_timed_region": n_timed,
+                "kernel_bracketed_p50": pct(bracket, 0.5),
                 "step_p10": pct(ss, 0.1), "step_p50": pct(ss, 0.5), "step_p90": pct(ss, 0.9), "step_samples": len(ss)}
 
 def stream_probe_gbs(nbytes=1 << 30):
@@ -547,6 +559,8 @@ def roofline_of(case, t, workload):
          "kernel": "splitkv_kernel", "kernel_avg_us": ksec * 1e6, "kernel_p10_us": t["kernel_p10"] * 1e6,
          "kernel_median_us": t["kernel_p50"] * 1e6, "kernel_p90_us": t["kernel_p90"] * 1e6,
          "kernel_samples": t["kernel_samples"], "kernel_samples_in_timed_region": t["kernel_samples_in_timed_region"],
+         "kernel_timing": "HIP events attached to the kernel's dispatch (begin / end of the kernel on the launch stream)",
+         "kernel_median_us_between_event_records": t["kernel_bracketed_p50"] * 1e6,
          "t_hbm_us": t_hbm * 1e6, "t_mfma_us": t_mfma * 1e6, "hbm": hbm, "mfma": mfma}
     return r
 

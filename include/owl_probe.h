@@ -86,6 +86,24 @@ owl_status owl_step_probe(int32_t variant, const void *src, int32_t iters, float
 owl_status owl_selftest_quad_max(const float *in64, float *out64, void *stream);
 
 /*
+ * The split-KV pass of the verify step, i.e. OWL_PHASE_SPLIT of
+ * owl_verify_attn_phases with the same arguments, with two HIP events attached to the kernel's own dispatch:
+ * start_event is stamped when the kernel begins, stop_event when its last
+ * workgroup has ended, so their difference is the duration of the kernel alone
+ * (what a kernel trace reports), without the few microseconds that a pair of
+ * hipEventRecord calls around a launch adds.  The events come from
+ * owl_probe_event_create (plain hipEvent_t behind a void*); read them with
+ * owl_probe_event_elapsed_ms, which waits for stop_event on the host.
+ */
+owl_status owl_verify_attn_split_timed(const owl_verify_desc *desc, const void *q, const void *k_cache,
+                                       const void *v_cache, const int32_t *page_table, const int32_t *ctx_lens,
+                                       const int32_t *tree_parent, void *out, void *workspace, size_t workspace_bytes,
+                                       uint32_t *dev_status, void *stream, void *start_event, void *stop_event);
+owl_status owl_probe_event_create(void **event);
+owl_status owl_probe_event_destroy(void *event);
+owl_status owl_probe_event_elapsed_ms(void *start_event, void *stop_event, float *ms_host);
+
+/*
  * Per-workgroup timeline of the split-KV pass.  With a device buffer of
  * 10 * n_workgroups int64, later owl_verify_attn calls whose split-KV grid has
  * at most n_workgroups workgroups (owl_plan.n_workgroups) and whose shape has a

@@ -15,7 +15,10 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "owl_oracle.c")
-_LIB = os.path.join(_HERE, "libowl_oracle.so")
+# OWL_ORACLE_SANITIZE=1 selects a build with AddressSanitizer and UndefinedBehaviorSanitizer (the
+# process must then run with gcc's libasan preloaded; tests/test_sanitizers.py does that)
+_SANITIZE = os.environ.get("OWL_ORACLE_SANITIZE", "") == "1"
+_LIB = os.path.join(_HERE, "libowl_oracle_san.so" if _SANITIZE else "libowl_oracle.so")
 _lib = None
 
 
@@ -37,8 +40,10 @@ class _Problem(ctypes.Structure):
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (OpenMP over output rows)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        extra = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                 "-fno-omit-frame-pointer"] if _SANITIZE else ["-O2"]
         subprocess.check_call(
-            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
+            ["gcc", *extra, "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
              "-o", _LIB, _SRC, "-lm"])
     return _LIB
 

@@ -11,7 +11,9 @@ import os
 from typing import Optional
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libowl.so")
+# OWL_LIB_PATH points the binding at another build of the same library (the host-sanitizer build
+# of tests/test_sanitizers.py); there is still no fallback if the file is missing.
+LIB_PATH = os.environ.get("OWL_LIB_PATH") or os.path.join(_PKG, "libowl.so")
 
 OWL_BF16, OWL_F32, OWL_F16 = 0, 1, 2
 OWL_OK = 0
@@ -37,7 +39,8 @@ EXPORTS = (
 # ... and in include/owl_probe.h (measurement and self-test aids)
 PROBE_EXPORTS = (
     "owl_stream_read_probe", "owl_gather_read_probe", "owl_mfma_probe", "owl_selftest_quad_max",
-    "owl_debug_set_timeline", "owl_step_probe",
+    "owl_debug_set_timeline", "owl_step_probe", "owl_verify_attn_split_timed", "owl_probe_event_create",
+    "owl_probe_event_destroy", "owl_probe_event_elapsed_ms",
 )
 OWL_NOALLOC_SCRATCH_BYTES = 48 << 20
 
@@ -127,6 +130,15 @@ def lib() -> ctypes.CDLL:
         l.owl_gather_read_probe.argtypes = [vp, vp, i32, vp, i32, vp]
         l.owl_debug_set_timeline.restype = ctypes.c_int
         l.owl_debug_set_timeline.argtypes = [vp, i64]
+        l.owl_verify_attn_split_timed.restype = ctypes.c_int
+        l.owl_verify_attn_split_timed.argtypes = [ctypes.POINTER(VerifyDesc), vp, vp, vp, vp, vp, vp, vp,
+                                                  vp, ctypes.c_size_t, vp, vp, vp, vp]
+        l.owl_probe_event_create.restype = ctypes.c_int
+        l.owl_probe_event_create.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        l.owl_probe_event_destroy.restype = ctypes.c_int
+        l.owl_probe_event_destroy.argtypes = [vp]
+        l.owl_probe_event_elapsed_ms.restype = ctypes.c_int
+        l.owl_probe_event_elapsed_ms.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_float)]
         l.owl_step_probe.restype = ctypes.c_int
         l.owl_step_probe.argtypes = [i32, vp, i32, vp, vp, i32, vp]
         l.owl_selftest_quad_max.restype = ctypes.c_int
@@ -260,6 +272,38 @@ def owl_debug_set_timeline(buffer) -> None:
     number of workgroups it has room for), or None to switch the recording off."""
     n = 0 if buffer is None else int(buffer.numel()) // 10
     _check(lib().owl_debug_set_timeline(_ptr(buffer), n), "owl_debug_set_timeline")
+
+
+class KernelTimer:
+    """A pair of HIP events that the library attaches to the dispatch of the split-KV kernel itself."""
+
+    def __init__(self):
+        a, b = ctypes.c_void_p(), ctypes.c_void_p()
+        _check(lib().owl_probe_event_create(ctypes.byref(a)), "owl_probe_event_create")
+        _check(lib().owl_probe_event_create(ctypes.byref(b)), "owl_probe_event_create")
+        self.start, self.stop = a, b
+
+    def elapsed_ms(self) -> float:
+        ms = ctypes.c_float(0.0)
+        _check(lib().owl_probe_event_elapsed_ms(self.start, self.stop, ctypes.byref(ms)), "owl_probe_event_elapsed_ms")
+        return float(ms.value)
+
+    def __del__(self):
+        try:
+            lib().owl_probe_event_destroy(self.start)
+            lib().owl_probe_event_destroy(self.stop)
+        except Exception:
+            pass
+
+
+def owl_verify_attn_split_timed(desc: VerifyDesc, q, k_cache, v_cache, page_table, ctx_lens, tree_parent, out,
+                                workspace, timer: KernelTimer, dev_status=None, stream: Optional[int] = None) -> None:
+    rc = lib().owl_verify_attn_split_timed(ctypes.byref(desc), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                           _ptr(page_table), _ptr(ctx_lens), _ptr(tree_parent), _ptr(out),
+                                           _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                           _ptr(dev_status), _stream() if stream is None else stream,
+                                           timer.start, timer.stop)
+    _check(rc, "owl_verify_attn_split_timed")
 
 
 STEP_PROBE_VARIANTS = (

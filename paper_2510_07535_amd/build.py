@@ -56,5 +56,45 @@ def build_library(extra_flags=(), verbose: bool = False) -> str:
     return OUT
 
 
+HOST_SOURCES = ["owl_api.hip", "owl_probe.hip"]       # argument checks, planning, hooks: the host logic
+HOST_SAN_OUT = os.path.join(PKG, "libowl_hostsan.so")
+
+
+def build_host_sanitized() -> str:
+    """libowl_hostsan.so: the translation units that hold the host logic rebuilt with AddressSanitizer and
+    UndefinedBehaviorSanitizer on the HOST side only (device code is not instrumented), linked with the
+    ordinary objects of the kernel files.  For host-only tests; needs clang's ASan runtime preloaded."""
+    os.makedirs(OBJ, exist_ok=True)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+    objs = []
+    for src in SOURCES:
+        obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+        if src in HOST_SOURCES:
+            obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".hostsan.o")
+            cmd = [hipcc(), *FLAGS, *san, "-c", os.path.join(CSRC, src), "-o", obj]
+            r = subprocess.run(cmd, capture_output=True, text=True)
+            if r.returncode != 0:
+                raise RuntimeError(f"hipcc (host sanitizers) failed for {src}:\n{r.stderr}")
+        elif not os.path.exists(obj):
+            obj = _compile(src, [])
+        objs.append(obj)
+    # link only (no device compilation on this line): host sanitizer runtimes, GPU sanitizing explicitly off
+    subprocess.check_call([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-sanitize",
+                           "-fsanitize=address", "-fsanitize=undefined", "-shared-libsan", "-o", HOST_SAN_OUT, *objs])
+    return HOST_SAN_OUT
+
+
+def asan_runtime() -> str:
+    """Path of clang's shared AddressSanitizer runtime (to be preloaded into the python process)."""
+    out = subprocess.run([hipcc(), "-print-file-name=libclang_rt.asan-x86_64.so"], capture_output=True, text=True)
+    path = out.stdout.strip().splitlines()[-1] if out.stdout.strip() else ""
+    if not os.path.isabs(path) or not os.path.exists(path):
+        import glob
+        cands = glob.glob("/opt/rocm/lib/llvm/lib/clang/*/lib/linux/libclang_rt.asan-x86_64.so")
+        path = cands[0] if cands else ""
+    return path
+
+
 if __name__ == "__main__":
     build_library(sys.argv[1:], verbose=True)

@@ -5,6 +5,7 @@
 #include <mutex>
 
 #include "owl_internal.h"
+#include "owl_probe.h"
 
 using namespace owl;
 
@@ -241,7 +242,7 @@ static owl_status verify_impl(const owl_verify_desc *desc, const void *q, const 
                               const void *v_cache, const int32_t *page_table, const int32_t *ctx_lens,
                               const int32_t *tree_parent, const int32_t *n_draft_seq, void *out,
                               void *workspace, size_t workspace_bytes, uint32_t *dev_status, void *stream,
-                              int32_t phases);
+                              int32_t phases, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
 owl_status owl_verify_attn_phases(const owl_verify_desc *desc, const void *q, const void *k_cache,
                                   const void *v_cache, const int32_t *page_table,
@@ -268,7 +269,7 @@ static owl_status verify_impl(const owl_verify_desc *desc, const void *q, const 
                               const void *v_cache, const int32_t *page_table, const int32_t *ctx_lens,
                               const int32_t *tree_parent, const int32_t *n_draft_seq, void *out,
                               void *workspace, size_t workspace_bytes, uint32_t *dev_status, void *stream,
-                              int32_t phases)
+                              int32_t phases, hipEvent_t ev_start, hipEvent_t ev_stop)
 {
     if (phases < 1 || phases > OWL_PHASE_ALL) return OWL_ERR_INVALID_ARG;
     FullPlan fp;
@@ -322,12 +323,47 @@ static owl_status verify_impl(const owl_verify_desc *desc, const void *q, const 
     p.item_slots = (int32_t)fp.item_slots;
     const dim3 grid = fp.grid;
     if (phases & OWL_PHASE_SPLIT) {
-        variant->launch(p, grid, s);
+        variant->launch(p, grid, s, ev_start, ev_stop);
         if (hipGetLastError() != hipSuccess) return OWL_ERR_HIP;
     }
     if (phases & OWL_PHASE_COMBINE)
         if (launch_combine(p, desc->head_dim, s) != hipSuccess) return OWL_ERR_HIP;
     return OWL_OK;
+}
+
+// ---- measurement aids that need the verify path itself (declared in owl_probe.h) ----
+owl_status owl_verify_attn_split_timed(const owl_verify_desc *desc, const void *q, const void *k_cache,
+                                       const void *v_cache, const int32_t *page_table, const int32_t *ctx_lens,
+                                       const int32_t *tree_parent, void *out, void *workspace, size_t workspace_bytes,
+                                       uint32_t *dev_status, void *stream, void *start_event, void *stop_event)
+{
+    if (!start_event || !stop_event) return OWL_ERR_INVALID_ARG;
+    return verify_impl(desc, q, k_cache, v_cache, page_table, ctx_lens, tree_parent, nullptr, out, workspace,
+                       workspace_bytes, dev_status, stream, OWL_PHASE_SPLIT, static_cast<hipEvent_t>(start_event),
+                       static_cast<hipEvent_t>(stop_event));
+}
+
+owl_status owl_probe_event_create(void **event)
+{
+    if (!event) return OWL_ERR_INVALID_ARG;
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return OWL_ERR_HIP;
+    *event = e;
+    return OWL_OK;
+}
+
+owl_status owl_probe_event_destroy(void *event)
+{
+    if (!event) return OWL_ERR_INVALID_ARG;
+    return hipEventDestroy(static_cast<hipEvent_t>(event)) == hipSuccess ? OWL_OK : OWL_ERR_HIP;
+}
+
+owl_status owl_probe_event_elapsed_ms(void *start_event, void *stop_event, float *ms_host)
+{
+    if (!start_event || !stop_event || !ms_host) return OWL_ERR_INVALID_ARG;
+    if (hipEventSynchronize(static_cast<hipEvent_t>(stop_event)) != hipSuccess) return OWL_ERR_HIP;
+    return hipEventElapsedTime(ms_host, static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event)) == hipSuccess
+               ? OWL_OK : OWL_ERR_HIP;
 }
 
 owl_status owl_verify_attn_init(const owl_verify_desc *desc)

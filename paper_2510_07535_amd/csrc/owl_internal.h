@@ -48,7 +48,8 @@ struct Variant {
     int dtype, D, tpw, wr, wk;
     bool timeline;
     size_t lds_bytes;
-    void (*launch)(const KParams &, dim3 grid, hipStream_t);
+    // start / stop: optional events attached to the kernel's own dispatch (its begin and end), else null
+    void (*launch)(const KParams &, dim3 grid, hipStream_t, hipEvent_t start, hipEvent_t stop);
     const void *func;     // for hipFuncSetAttribute
 };
 

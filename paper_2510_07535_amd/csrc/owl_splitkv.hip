@@ -41,6 +41,8 @@
 // Visibility (Sec. 3.2.2, Decode Stage): every row sees the whole prefix; among
 // the drafts, row (i, .) sees node j iff j is on i's root path, i included.
 // Only 32-key steps that reach past the prefix take the masked ("careful") path.
+#include <hip/hip_ext.h>
+
 #include <type_traits>
 
 #include "owl_device.h"
@@ -1045,10 +1047,13 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
 // instantiations
 // ---------------------------------------------------------------------------
 template <typename T, int D, int TPW, int WR, int WK, bool TL>
-static void launch_variant(const KParams &p, dim3 grid, hipStream_t s)
+static void launch_variant(const KParams &p, dim3 grid, hipStream_t s, hipEvent_t start, hipEvent_t stop)
 {
     using GEO = Geo<T, D, TPW, WR, WK>;
-    hipLaunchKernelGGL((splitkv_kernel<T, D, TPW, WR, WK, TL>), grid, dim3(kThreads), GEO::LDS, s, p);
+    if (start || stop)
+        hipExtLaunchKernelGGL((splitkv_kernel<T, D, TPW, WR, WK, TL>), grid, dim3(kThreads), GEO::LDS, s, start, stop, 0, p);
+    else
+        hipLaunchKernelGGL((splitkv_kernel<T, D, TPW, WR, WK, TL>), grid, dim3(kThreads), GEO::LDS, s, p);
 }
 
 #define OWL_VARIANT(DT, T, D, TPW, WR, WK, TL)                                          \

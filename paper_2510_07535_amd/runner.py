@@ -58,6 +58,12 @@ class VerifyStep:
             B.owl_verify_attn_phases(*args, stream=stream, phases=phases)
         return self.out
 
+    def run_split_timed(self, timer, k=None, v=None, stream: Optional[int] = None) -> None:
+        """The split-KV pass alone with ``timer``'s events attached to the kernel's dispatch (measurement)."""
+        B.owl_verify_attn_split_timed(self.desc, self.q, self.k if k is None else k, self.v if v is None else v,
+                                      self.page_table, self.ctx_lens, self.tree_parent, self.out, self.workspace,
+                                      timer, self.status, stream=stream)
+
     def result(self) -> np.ndarray:
         """``out`` on the host: float32, or the uint16 bit patterns of a 16-bit output type."""
         torch.cuda.synchronize(self.device)
