@@ -14,7 +14,7 @@ Prints ONE JSON line.  `value` is algorithmic KV bytes per second
 (sum_b (L_b + N) * Hkv * D * 2 tensors * 2 bytes, divided by the time of the
 whole step); `ms_per_step` is the verify-step time: wall clock over exactly
 --steps steps between two synchronisations.  `roofline` prices the split-KV
-kernel alone from HIP events attached to its dispatch (every fourth step of
+kernel alone from HIP events attached to its dispatch (every eighth step of
 the timed region, plus a sampling pass after it so that there are at least 32
 samples whatever --steps is) against whichever of the two roofs bounds the
 shape: 8 TB/s of HBM over the algorithmic K/V bytes or 2.5 PFLOP/s of dense
@@ -133,7 +133,7 @@ class Rotating:
         self.step.run_split_timed(timer, k=k, v=v)
 
     def time_steps_with_kernel(self, steps, warmup, settle_ms=0.0):
-        """The timed region (wall clock over exactly `steps` steps).  In every fourth step the split-KV
+        """The timed region (wall clock over exactly `steps` steps).  In every eighth step the split-KV
         kernel is launched with a pair of HIP events attached to its own dispatch (begin and end of
         the kernel on the launch stream; such a step is enqueued as its two phases: the same
         kernels).  Then, outside the region: more such launches until there are MIN_KERNEL_SAMPLES, a
@@ -142,7 +142,7 @@ class Rotating:
         times.  Returns a dict of seconds."""
         torch = self.torch
         from paper_2510_07535_amd.binding import KernelTimer
-        every = 4
+        every = 8                                        # a timed launch costs its step ~10 us of host-side bookkeeping
         timers = [KernelTimer() for _ in range(max((steps + every - 1) // every, MIN_KERNEL_SAMPLES))]
         n_timed = (steps + every - 1) // every
         self.settle(settle_ms)
@@ -530,6 +530,7 @@ def bench_draft_sweep(ctx=65536, counts=(1, 4, 8, 16, 24, 32, 48, 60)):
         tree = W.chain_tree(n) if n <= 8 else W.random_tree(n, 6, rng)
         case = W.make_case(f"sweep_n{n}", 9, dtype=W.DT_BF16, Hq=32, Hkv=8, D=128, ctx_lens=[ctx], trees=[tree])
         rot = Rotating(case)
+        rot.settle(300)
         sec = rot.time_steps(150, 20)
         out.append({"n_draft": n, "rows_per_kv": rot.step.plan.rows_per_kv, "ctx": ctx, "us_per_step": sec * 1e6,
                     "GBps": rot.kv_bytes / sec / 1e9})

@@ -72,7 +72,7 @@ class Plan(ctypes.Structure):
     ]
 
     def as_dict(self):
-        return {n: getattr(self, n) for n, _ in self._fields_}
+        return {n: getattr(self, n) for n, _ in self._fields_ if not n.startswith("reserved")}
 
 
 class DrafterDesc(ctypes.Structure):

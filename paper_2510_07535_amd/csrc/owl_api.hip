@@ -140,6 +140,7 @@ owl_status make_plan(const owl_verify_desc *d, FullPlan *fp)
     fp->part_ml_bytes = align_up(slots * 32 * sizeof(float), 256);
     fp->variant = v;
     owl_plan &pl = fp->pub;
+    pl.reserved_ = 0;
     pl.split_tokens = (int32_t)C;
     pl.max_splits = (int32_t)max_splits;
     pl.rows_per_kv = R;
