@@ -95,9 +95,22 @@ typedef struct owl_verify_desc {
                                 /* the fp32 result rounded to nearest even on the way out */
     int64_t kv_stride_page, kv_stride_head, kv_stride_token;
     int64_t n_pool_pages;       /* pages in k_cache / v_cache (bounds for page ids)      */
-    int32_t flags;              /* no flag is defined: set to 0                          */
+    int32_t flags;              /* bit set of OWL_FLAG_*, 0 = none                       */
     int32_t reserved_;          /* set to 0                                              */
 } owl_verify_desc;
+
+/*
+ * OWL_FLAG_FP32_PARTIALS (16-bit qkv_dtype only; fp32 inputs always behave so):
+ * the split-KV pass hands its per-split results to the combine as raw fp32
+ * accumulators.  By default it hands them over normalised and in fp16 (each row
+ * divided by its row sum and by its largest magnitude, which is kept in fp32):
+ * half the bytes to write and read back, for a rounding of 2^-12 of a row's
+ * largest component, far below what the 16-bit softmax weights cost already.
+ * With the flag the whole path adds in fp32 only, so that results that are
+ * exactly representable (e.g. the mean of small integers over a power-of-two
+ * number of rows) come out exact; the workspace is larger.
+ */
+#define OWL_FLAG_FP32_PARTIALS 1
 
 /* What the library decided for a descriptor; informational (bench, tests). */
 typedef struct owl_plan {

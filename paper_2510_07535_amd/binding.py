@@ -25,6 +25,8 @@ OWL_DEV_BAD_TOKEN, OWL_DEV_BAD_ROW = 32, 64
 OWL_DRAFTER_PROJ, OWL_DRAFTER_GATES, OWL_DRAFTER_ALL = 1, 2, 3
 OWL_W_ROWS, OWL_W_TILED = 0, 1
 
+OWL_FLAG_FP32_PARTIALS = 1
+
 # entry points declared in include/owl.h (the product interface) ...
 EXPORTS = (
     "owl_verify_attn_plan", "owl_verify_attn_workspace_size", "owl_verify_attn",

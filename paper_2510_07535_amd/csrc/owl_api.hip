@@ -44,7 +44,7 @@ owl_status check_desc(const owl_verify_desc *d)
     if (d->max_pages_per_seq < 0 || d->n_pool_pages < 1) return OWL_ERR_INVALID_ARG;
     if (d->split_tokens < 0) return OWL_ERR_INVALID_ARG;
     if (d->out_dtype != OWL_F32 && d->out_dtype != OWL_BF16 && d->out_dtype != OWL_F16) return OWL_ERR_UNSUPPORTED;
-    if (d->flags != 0 || d->reserved_ != 0) return OWL_ERR_INVALID_ARG;
+    if ((d->flags & ~(int32_t)OWL_FLAG_FP32_PARTIALS) != 0 || d->reserved_ != 0) return OWL_ERR_INVALID_ARG;
     if (!(d->scale > 0.0f) || !isfinite(d->scale)) return OWL_ERR_INVALID_ARG;
     const int es = elem_size(d->qkv_dtype);
     const int64_t st[3] = {d->kv_stride_page, d->kv_stride_head, d->kv_stride_token};
@@ -59,6 +59,7 @@ struct FullPlan {
     owl_plan pub;
     const Variant *variant;
     size_t part_o_bytes, part_ml_bytes;
+    bool half_partials;       // normalised fp16 partials (16-bit inputs unless the caller asks for fp32 ones)
     int32_t adapt, c_min;
     int64_t item_slots;       // adapt == 2: (sequence, split) pairs the grid has room for
     dim3 grid;                // of the split-KV pass
@@ -136,8 +137,9 @@ owl_status make_plan(const owl_verify_desc *d, FullPlan *fp)
     }
 
     const size_t slots = (size_t)d->batch * d->n_kv_heads * (size_t)max_splits * RT;
-    fp->part_o_bytes = align_up(slots * (size_t)d->head_dim * kRowTile * sizeof(float), 256);
-    fp->part_ml_bytes = align_up(slots * 32 * sizeof(float), 256);
+    fp->half_partials = d->qkv_dtype != OWL_F32 && !(d->flags & OWL_FLAG_FP32_PARTIALS);
+    fp->part_o_bytes = align_up(slots * (size_t)d->head_dim * kRowTile * (fp->half_partials ? 2 : 4), 256);
+    fp->part_ml_bytes = align_up(slots * kPartMl * sizeof(float), 256);
     fp->variant = v;
     owl_plan &pl = fp->pub;
     pl.reserved_ = 0;
@@ -302,7 +304,8 @@ static owl_status verify_impl(const owl_verify_desc *desc, const void *q, const 
     p.q = q; p.k = k_cache; p.v = v_cache;
     p.page_table = page_table; p.ctx_lens = ctx_lens; p.parent = tree_parent;
     p.n_draft_seq = n_draft_seq;
-    p.part_o = reinterpret_cast<float *>(ws);
+    p.part_o = ws;
+    p.half_partials = fp.half_partials ? 1 : 0;
     p.part_ml = reinterpret_cast<float *>(ws + fp.part_o_bytes);
     p.dev_c = reinterpret_cast<int32_t *>(ws + fp.part_o_bytes + fp.part_ml_bytes);
     p.out = out;
@@ -328,7 +331,7 @@ static owl_status verify_impl(const owl_verify_desc *desc, const void *q, const 
         if (hipGetLastError() != hipSuccess) return OWL_ERR_HIP;
     }
     if (phases & OWL_PHASE_COMBINE)
-        if (launch_combine(p, desc->head_dim, s) != hipSuccess) return OWL_ERR_HIP;
+        if (launch_combine(p, desc->head_dim, fp.half_partials, s) != hipSuccess) return OWL_ERR_HIP;
     return OWL_OK;
 }
 

@@ -10,14 +10,25 @@ namespace owl {
 // visible keys (x = score * log2 e; m_s is the reference the split happened to
 // use, not necessarily its max).  With M = max_s m_s:
 //     out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
-// Partials are stored as raw accumulator fragments: float4 [slot][u][lane]
-// holds channels 16*u + 4*quad .. +3 of row lane%16.
+// For fp32 inputs the partials are the raw accumulator fragments, float4
+// [slot][u][lane] = channels 16*u + 4*quad .. +3 of row lane%16.  For 16-bit
+// inputs (HALF) a row of a partial is stored normalised, O_s / (l_s s_s) with s_s
+// its largest magnitude, as fp16: uint4 [slot][u/2][lane] holds the lane's four
+// channels of tiles u and u + 1; the weight of split s is then 2^(m_s - M) l_s s_s.
 //
 // One workgroup per (sequence, KV head, 16-row tile, pair of channel tiles);
 // its four waves take every fourth split, reduce their share against their own
 // running maximum, and are merged through LDS with the same formula.
 // ---------------------------------------------------------------------------
-template <int D>
+typedef _Float16 c_f16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float2 unpack_half2(uint32_t w)
+{
+    const c_f16x2 h = __builtin_bit_cast(c_f16x2, w);
+    return make_float2((float)h[0], (float)h[1]);
+}
+
+template <int D, bool HALF>
 __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
 {
     constexpr int NT = D / 16, UPW = 2;              // channel tiles per workgroup
@@ -47,17 +58,26 @@ __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
     // memory latency once per batch rather than once per split (up to 32 splits: once).
     constexpr int kInFlight = 8;
     for (int s0 = w; s0 < ns; s0 += 4 * kInFlight) {
-        float ms[kInFlight], ls[kInFlight];
+        float ms[kInFlight], ls[kInFlight], os[kInFlight];
         float4 x[kInFlight][UPW];
 #pragma unroll
         for (int k = 0; k < kInFlight; ++k) {
             const int s = min(s0 + 4 * k, ns - 1);           // past the end: re-read the last split, not merged
             const size_t slot = slot0 + (size_t)s * p.RT;
-            ms[k] = p.part_ml[slot * 32 + j];
-            ls[k] = p.part_ml[slot * 32 + 16 + j];
-            const float4 *po = reinterpret_cast<const float4 *>(p.part_o) + slot * (size_t)(NT * 64) + lane;
+            ms[k] = p.part_ml[slot * kPartMl + j];
+            ls[k] = p.part_ml[slot * kPartMl + 16 + j];
+            if constexpr (HALF) {
+                static_assert(UPW == 2, "one 16-byte piece per lane holds a pair of channel tiles");
+                os[k] = ls[k] * p.part_ml[slot * kPartMl + 32 + j];   // the stored rows are O / (l s)
+                const uint4 h = static_cast<const uint4 *>(p.part_o)[slot * (size_t)(NT / 2 * 64) + (u0 / 2) * 64 + lane];
+                const float2 a0 = unpack_half2(h.x), a1 = unpack_half2(h.y), b0 = unpack_half2(h.z), b1 = unpack_half2(h.w);
+                x[k][0] = make_float4(a0.x, a0.y, a1.x, a1.y);
+                x[k][1] = make_float4(b0.x, b0.y, b1.x, b1.y);
+            } else {
+                const float4 *po = static_cast<const float4 *>(p.part_o) + slot * (size_t)(NT * 64) + lane;
 #pragma unroll
-            for (int u = 0; u < UPW; ++u) x[k][u] = po[(u0 + u) * 64];
+                for (int u = 0; u < UPW; ++u) x[k][u] = po[(u0 + u) * 64];
+            }
         }
 #pragma unroll
         for (int k = 0; k < kInFlight; ++k) {
@@ -67,10 +87,11 @@ __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
                 const float c = __builtin_amdgcn_exp2f(ms[k] - mn);
                 mw = mn;
                 lw = lw * a + ls[k] * c;
+                const float co = HALF ? c * os[k] : c;       // weight of the stored O fragment
 #pragma unroll
                 for (int u = 0; u < UPW; ++u) {
-                    acc[u].x = acc[u].x * a + x[k][u].x * c; acc[u].y = acc[u].y * a + x[k][u].y * c;
-                    acc[u].z = acc[u].z * a + x[k][u].z * c; acc[u].w = acc[u].w * a + x[k][u].w * c;
+                    acc[u].x = acc[u].x * a + x[k][u].x * co; acc[u].y = acc[u].y * a + x[k][u].y * co;
+                    acc[u].z = acc[u].z * a + x[k][u].z * co; acc[u].w = acc[u].w * a + x[k][u].w * co;
                 }
             }
         }
@@ -111,13 +132,13 @@ __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
                    p.out_dtype);
 }
 
-hipError_t launch_combine(const KParams &p, int D, hipStream_t s)
+hipError_t launch_combine(const KParams &p, int D, bool half_partials, hipStream_t s)
 {
     dim3 grid(p.RT * (D / 32), p.Hkv, p.B);
-    if (D == 128)
-        hipLaunchKernelGGL(combine_kernel<128>, grid, dim3(256), 0, s, p);
-    else
-        hipLaunchKernelGGL(combine_kernel<64>, grid, dim3(256), 0, s, p);
+    if (D == 128 && half_partials) hipLaunchKernelGGL((combine_kernel<128, true>), grid, dim3(256), 0, s, p);
+    else if (D == 128) hipLaunchKernelGGL((combine_kernel<128, false>), grid, dim3(256), 0, s, p);
+    else if (half_partials) hipLaunchKernelGGL((combine_kernel<64, true>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((combine_kernel<64, false>), grid, dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
@@ -195,8 +216,10 @@ hipError_t launch_gather(const owl_verify_desc &d, const void *cache, const int3
 hipError_t load_aux_kernels()
 {
     hipFuncAttributes a;
-    hipError_t e = hipFuncGetAttributes(&a, reinterpret_cast<const void *>(&combine_kernel<128>));
-    if (e == hipSuccess) e = hipFuncGetAttributes(&a, reinterpret_cast<const void *>(&combine_kernel<64>));
+    hipError_t e = hipFuncGetAttributes(&a, reinterpret_cast<const void *>(&combine_kernel<128, true>));
+    if (e == hipSuccess) e = hipFuncGetAttributes(&a, reinterpret_cast<const void *>(&combine_kernel<128, false>));
+    if (e == hipSuccess) e = hipFuncGetAttributes(&a, reinterpret_cast<const void *>(&combine_kernel<64, true>));
+    if (e == hipSuccess) e = hipFuncGetAttributes(&a, reinterpret_cast<const void *>(&combine_kernel<64, false>));
     return e;
 }
 

@@ -15,13 +15,24 @@ constexpr int kMaxSplitTokens = 16384;    // bounds the per-workgroup page list 
 constexpr int kMaxPagesPerSplit = kMaxSplitTokens / kPage;
 constexpr int kSplitQuantum = 64;         // split_tokens is a multiple of every stage size
 
+// Format of a split's partial, per 16-row tile ("slot").
+//   fp32 inputs, and 16-bit inputs with OWL_FLAG_FP32_PARTIALS:
+//                  O fragments as they stand, float4 [slot][channel tile][lane]; (m, l) in part_ml.
+//   16-bit inputs: the NORMALISED output O / l of each row (a convex combination of V rows, so bounded by
+//                  them), divided by s = its largest magnitude over the row's channels, as fp16:
+//                  uint4 [slot][pair of channel tiles][lane] = 2 x 4 halves; (m, l, s) in part_ml.  Half the
+//                  bytes to write and to read back; a value is stored to 2^-12 of its row's largest
+//                  component whatever the magnitude of V, far below the bf16 rounding of P.
+constexpr int kPartMl = 48;               // floats of part_ml per slot: m[16], l[16], s[16]
+
 // Everything a kernel needs, passed by value.
 struct KParams {
     const void *q, *k, *v;
     const int32_t *page_table, *ctx_lens, *parent;
     const int32_t *n_draft_seq;   // optional [B]: drafted tokens of each sequence (<= N), else null = N everywhere
-    float *part_o;        // split partials: accumulator fragments
-    float *part_ml;       // split partials: running reference m and row sum l
+    void *part_o;         // split partials: accumulator fragments (see kPartMl below)
+    int32_t half_partials;// 1: normalised fp16 partials (16-bit inputs, the default), 0: raw fp32 fragments
+    float *part_ml;       // split partials: per row reference m, row sum l and, for 16-bit partials, scale s
     void *out;            // [B][N][Hq][D] in out_dtype
     int32_t out_dtype;    // OWL_F32, OWL_BF16 or OWL_F16
     uint32_t *dev_status;
@@ -65,7 +76,7 @@ TimelineHook timeline_hook();
 void set_timeline_hook(long long *buffer, long long capacity);
 hipError_t load_aux_kernels();
 
-hipError_t launch_combine(const KParams &p, int D, hipStream_t s);
+hipError_t launch_combine(const KParams &p, int D, bool half_partials, hipStream_t s);
 hipError_t launch_prepare(const int32_t *parent, const int32_t *ctx_lens, int B, int n, int32_t *parent2,
                           uint64_t *anc, int32_t *depth, int32_t *pos, uint32_t *status, hipStream_t s);
 hipError_t launch_accept(const int32_t *tokens, const int32_t *parent, const int32_t *target_root,

@@ -1019,21 +1019,51 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
         }
     }
 
-    // ---- write this split's partial: accumulator fragments as they are ----
-    // float4 [slot][u][lane] = channels 16*u + 4*quad .. +3 of row lane%16.
+    // ---- write this split's partial ----
+    // fp32 partials (fp32 inputs, or on request): the accumulator fragments as they are, float4 [slot][u][lane] =
+    // channels 16*u + 4*quad .. +3 of row lane%16.  Otherwise: each row normalised by its row sum and by its largest magnitude s, as fp16,
+    // uint4 [slot][u/2][lane] = the four halves of channel tile u (even) and of u + 1; (m, l, s) beside it.
     if (wk == 0) {
 #pragma unroll
         for (int t = 0; t < TPW; ++t) {
             const int tg = rg * (WR * TPW) + t * WR + wr;
             if (tg >= p.RT) continue;
             const size_t slot = (((size_t)b * p.Hkv + g) * p.max_splits + c) * p.RT + tg;
-            float4 *po = reinterpret_cast<float4 *>(p.part_o) + slot * (size_t)(NT * 64) + lane;
+            const float l = O[t][NT][0];
+            if (kF32 || !p.half_partials) {                          // uniform over the launch
+                float4 *po = static_cast<float4 *>(p.part_o) + slot * (size_t)(NT * 64) + lane;
 #pragma unroll
-            for (int u = 0; u < NT; ++u)
-                po[u * 64] = make_float4(O[t][u][0], O[t][u][1], O[t][u][2], O[t][u][3]);
-            if (qd == 0) {
-                p.part_ml[slot * 32 + j] = m[t];
-                p.part_ml[slot * 32 + 16 + j] = O[t][NT][0];
+                for (int u = 0; u < NT; ++u)
+                    po[u * 64] = make_float4(O[t][u][0], O[t][u][1], O[t][u][2], O[t][u][3]);
+                if (qd == 0) {
+                    p.part_ml[slot * kPartMl + j] = m[t];
+                    p.part_ml[slot * kPartMl + 16 + j] = l;
+                    p.part_ml[slot * kPartMl + 32 + j] = 1.0f;
+                }
+            } else {
+                const float inv_l = l > 0.f ? 1.0f / l : 0.f;          // a row that saw no key: all zeros
+                float big = 0.f;
+#pragma unroll
+                for (int u = 0; u < NT; ++u)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        O[t][u][r] *= inv_l;
+                        big = fmaxf(big, fabsf(O[t][u][r]));
+                    }
+                big = quad_column_max(big);                             // over the four lanes that hold this row
+                const float inv_s = big > 0.f ? 1.0f / big : 0.f;
+                uint4 *po = static_cast<uint4 *>(p.part_o) + slot * (size_t)(NT / 2 * 64) + lane;
+#pragma unroll
+                for (int u = 0; u < NT; u += 2)
+                    po[(u / 2) * 64] = make_uint4(pack2<_Float16>(O[t][u][0] * inv_s, O[t][u][1] * inv_s),
+                                                   pack2<_Float16>(O[t][u][2] * inv_s, O[t][u][3] * inv_s),
+                                                   pack2<_Float16>(O[t][u + 1][0] * inv_s, O[t][u + 1][1] * inv_s),
+                                                   pack2<_Float16>(O[t][u + 1][2] * inv_s, O[t][u + 1][3] * inv_s));
+                if (qd == 0) {
+                    p.part_ml[slot * kPartMl + j] = m[t];
+                    p.part_ml[slot * kPartMl + 16 + j] = l;
+                    p.part_ml[slot * kPartMl + 32 + j] = big;
+                }
             }
         }
     }

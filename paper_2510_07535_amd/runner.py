@@ -21,7 +21,7 @@ def _to_dev(a: np.ndarray, device) -> torch.Tensor:
 
 class VerifyStep:
     def __init__(self, case: W.Case, device: str = "cuda:0", split_tokens: int = 0,
-                 max_ctx_len: Optional[int] = None, out_dtype: int = B.OWL_F32):
+                 max_ctx_len: Optional[int] = None, out_dtype: int = B.OWL_F32, flags: int = 0):
         self.case = case
         self.device = torch.device(device)
         self.q = _to_dev(case.q, self.device)
@@ -39,7 +39,7 @@ class VerifyStep:
             max_ctx_len=case.max_ctx_len if max_ctx_len is None else max_ctx_len,
             qkv_dtype=case.dtype, scale=case.scale, kv_stride_page=case.stride_page,
             kv_stride_head=case.stride_head, kv_stride_token=case.stride_token,
-            n_pool_pages=case.n_pool_pages, split_tokens=split_tokens, out_dtype=out_dtype)
+            n_pool_pages=case.n_pool_pages, split_tokens=split_tokens, out_dtype=out_dtype, flags=flags)
         self.plan = B.owl_verify_attn_plan(self.desc)
         self.workspace = torch.empty(max(self.plan.workspace_bytes, 256), dtype=torch.uint8,
                                      device=self.device)

@@ -241,12 +241,15 @@ def test_drafter_alpha_host():
 
 
 def test_output_type_and_reserved_fields():
-    for over, code in ((dict(out_dtype=7), B.OWL_ERR_UNSUPPORTED), (dict(flags=1), B.OWL_ERR_INVALID_ARG)):
+    for over, code in ((dict(out_dtype=7), B.OWL_ERR_UNSUPPORTED), (dict(flags=2), B.OWL_ERR_INVALID_ARG)):
         with pytest.raises(B.OwlError) as e:
             B.owl_verify_attn_plan(_good(**over))
         assert e.value.code == code
     for od in (B.OWL_F32, B.OWL_BF16, B.OWL_F16):
         B.owl_verify_attn_plan(_good(out_dtype=od))
+    # fp32 partials on request: a larger workspace, the same plan otherwise
+    assert (B.owl_verify_attn_workspace_size(_good(flags=B.OWL_FLAG_FP32_PARTIALS))
+            > B.owl_verify_attn_workspace_size(_good()))
 
 
 def test_init_and_noalloc_reject_before_touching_a_device():

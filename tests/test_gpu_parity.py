@@ -154,6 +154,9 @@ def test_split_count_invariance(oracle_mod):
         got, _ = _run(case, split_tokens=split)
         assert_close(got, want, case.dtype, f"split={split}")
         outs.append(got)
+        raw, _ = _run(case, split_tokens=split, flags=B.OWL_FLAG_FP32_PARTIALS)      # partials as fp32 accumulators
+        assert_close(raw, want, case.dtype, f"split={split}, fp32 partials")
+        assert np.abs(raw - got).max() < 2e-3
     for o in outs[1:]:
         assert np.abs(o - outs[0]).max() < 5e-3
 
@@ -197,7 +200,9 @@ def test_page_permutation_is_invisible():
 def test_zero_query_integer_values_exact_mean():
     """q = 0, small-integer V, L + depth a power of two for the chain's last
     node: every weight is exactly 1, so the mean must be exact in fp32 -- any
-    wrong, missing or doubled cache row shows up as a bit difference."""
+    wrong, missing or doubled cache row shows up as a bit difference.  Exactness
+    needs the partials in fp32 (OWL_FLAG_FP32_PARTIALS); the default partials,
+    normalised and in fp16, must still be within 2^-11 of a row's largest value."""
     N, L = 4, 4096 - 4
     case = W.make_case("exact", 204, dtype=W.DT_BF16, Hq=4, Hkv=2, D=128, ctx_lens=[L], trees=[W.chain_tree(N)])
     case.q[...] = 0
@@ -208,10 +213,13 @@ def test_zero_query_integer_values_exact_mean():
         page = int(case.page_table[0, pos // 16])
         case.v_pool[page, :, pos % 16, :] = W.store(vals[pos], W.DT_BF16)
     for split in (0, 128, 1024):
-        got, _ = _run(case, split_tokens=split)
         want = vals.sum(axis=0, dtype=np.float64) / T            # last node sees all T rows
+        got, _ = _run(case, split_tokens=split, flags=B.OWL_FLAG_FP32_PARTIALS)
         for h in range(4):
             assert np.array_equal(got[0, N - 1, h].astype(np.float64), want[h // 2]), split
+        got, _ = _run(case, split_tokens=split)
+        for h in range(4):
+            assert np.abs(got[0, N - 1, h] - want[h // 2]).max() <= 2.0 ** -11 * np.abs(want[h // 2]).max() + 1e-6, split
 
 
 def test_quad_max_lane_semantics():
