@@ -58,7 +58,7 @@ owl_status check_desc(const owl_verify_desc *d)
 struct FullPlan {
     owl_plan pub;
     const Variant *variant;
-    size_t part_o_bytes, part_ml_bytes;
+    size_t part_o_bytes, part_ml_bytes, plan_bytes;
     bool half_partials;       // normalised fp16 partials (16-bit inputs unless the caller asks for fp32 ones)
     int32_t adapt, c_min;
     int64_t item_slots;       // adapt == 2: (sequence, split) pairs the grid has room for
@@ -158,7 +158,8 @@ owl_status make_plan(const owl_verify_desc *d, FullPlan *fp)
         fp->grid = dim3(d->n_kv_heads * rgs, (unsigned)per_z, (unsigned)((fp->item_slots + per_z - 1) / per_z));
     }
     pl.n_workgroups = (int32_t)((int64_t)fp->grid.x * fp->grid.y * fp->grid.z);
-    pl.workspace_bytes = fp->part_o_bytes + fp->part_ml_bytes + 256;    // + the derived split size
+    fp->plan_bytes = align_up(((size_t)d->batch + 3) * sizeof(int32_t), 256);     // the batch plan
+    pl.workspace_bytes = fp->part_o_bytes + fp->part_ml_bytes + fp->plan_bytes;
     return OWL_OK;
 }
 
@@ -297,7 +298,7 @@ static owl_status verify_impl(const owl_verify_desc *desc, const void *q, const 
     st = ensure_lds_attr(variant);
     if (st != OWL_OK) return st;
 
-    // workspace: partial O | partial (m, l) | derived split size
+    // workspace: partial O | partial (m, l, s) | batch plan
     char *ws = static_cast<char *>(workspace);
     KParams p;
     memset(&p, 0, sizeof p);
@@ -327,6 +328,7 @@ static owl_status verify_impl(const owl_verify_desc *desc, const void *q, const 
     p.item_slots = (int32_t)fp.item_slots;
     const dim3 grid = fp.grid;
     if (phases & OWL_PHASE_SPLIT) {
+        if (p.adapt == 2 && launch_batch_plan(p, s) != hipSuccess) return OWL_ERR_HIP;
         variant->launch(p, grid, s, ev_start, ev_stop);
         if (hipGetLastError() != hipSuccess) return OWL_ERR_HIP;
     }

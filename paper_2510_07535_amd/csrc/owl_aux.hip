@@ -211,6 +211,44 @@ hipError_t launch_gather(const owl_verify_desc &d, const void *cache, const int3
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Batch plan (batches with a library-chosen split size): one wavefront derives the
+// split size from the actual lengths (batch_split_tokens) and numbers the
+// (sequence, split) pairs densely; the split-KV pass and the combine read the
+// result instead of deriving it once per workgroup (which cost every workgroup of
+// the batched benchmark shape 4 us).
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(64) batch_plan_kernel(const KParams p)
+{
+    const int lane = threadIdx.x;
+    const int C = batch_split_tokens(p);
+    int32_t *prefix = p.dev_c + kPlanHeader;
+    int base = 0;
+    for (int b0 = 0; b0 < p.B; b0 += 64) {
+        const bool live = b0 + lane < p.B;
+        const int n = live ? (seq_tokens(p, b0 + lane) + C - 1) / C : 0;
+        int scan = n;                                 // inclusive scan over the lanes
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int up = __shfl_up(scan, off);
+            if (lane >= off) scan += up;
+        }
+        if (live) prefix[b0 + lane] = base + scan - n;
+        base += __builtin_amdgcn_readlane(scan, 63);
+    }
+    if (lane == 0) {
+        prefix[p.B] = base;
+        p.dev_c[0] = C;
+        p.dev_c[1] = base;
+    }
+}
+
+hipError_t launch_batch_plan(const KParams &p, hipStream_t s)
+{
+    hipLaunchKernelGGL(batch_plan_kernel, dim3(1), dim3(64), 0, s, p);
+    return hipGetLastError();
+}
+
 // Makes the runtime resolve the combine kernels now, so that their first launch may happen
 // inside a stream capture.
 hipError_t load_aux_kernels()
@@ -220,6 +258,7 @@ hipError_t load_aux_kernels()
     if (e == hipSuccess) e = hipFuncGetAttributes(&a, reinterpret_cast<const void *>(&combine_kernel<128, false>));
     if (e == hipSuccess) e = hipFuncGetAttributes(&a, reinterpret_cast<const void *>(&combine_kernel<64, true>));
     if (e == hipSuccess) e = hipFuncGetAttributes(&a, reinterpret_cast<const void *>(&combine_kernel<64, false>));
+    if (e == hipSuccess) e = hipFuncGetAttributes(&a, reinterpret_cast<const void *>(&batch_plan_kernel));
     return e;
 }
 

@@ -160,27 +160,30 @@ __device__ __forceinline__ int batch_split_tokens(const KParams &p)
     return total <= p.item_slots ? C : p.C;
 }
 
-// The (sequence, split) pair that work item `id` of a batch stands for when the
-// items of all sequences are numbered densely, sequence by sequence, with splits
-// of C tokens: workgroups that have something to do then come first in launch
-// order and the surplus of the grid (sized for the worst case) trails behind,
-// instead of being dispatched in between and holding up the ones behind them.
-// Wave-uniform; false if id is beyond the last item.
-__device__ __forceinline__ bool batch_item(const KParams &p, int C, int id, int *b_out, int *c_out)
+// Layout of the batch plan that batch_plan_kernel leaves in the workspace (int32): [0] the split
+// size C derived from the lengths, [1] the number of (sequence, split) pairs, [2 + b] the pairs
+// of the sequences before b (b = 0 .. B).
+constexpr int kPlanHeader = 2;
+
+// The (sequence, split) pair that work item `id` of a batch stands for when the items of all
+// sequences are numbered densely, sequence by sequence: workgroups that have something to do then
+// come first in launch order and the surplus of the grid (sized for the worst case) trails behind,
+// instead of being dispatched in between and holding up the ones behind them.  Reads the plan; one
+// round trip for up to 64 sequences.  Wave-uniform; false if id is beyond the last item.
+__device__ __forceinline__ bool batch_item(const KParams &p, int id, int *b_out, int *c_out)
 {
     const int lane = threadIdx.x & 63;
-    int base = 0;
+    const int32_t *prefix = p.dev_c + kPlanHeader;
     for (int b0 = 0; b0 < p.B; b0 += 64) {
-        const int n = b0 + lane < p.B ? (seq_tokens(p, b0 + lane) + C - 1) / C : 0;
-        const int n_lane = min(p.B - b0, 64);
-        for (int l = 0; l < n_lane; ++l) {           // scalar walk over the chunk's sequences
-            const int nl = __builtin_amdgcn_readlane(n, l);
-            if (id < base + nl) {
-                *b_out = b0 + l;
-                *c_out = id - base;
-                return true;
-            }
-            base += nl;
+        const bool live = b0 + lane < p.B;
+        const int lo = live ? prefix[b0 + lane] : 0x7fffffff;
+        const int up = live ? prefix[b0 + lane + 1] : 0x7fffffff;
+        const unsigned long long hit = __ballot(live && id >= lo && id < up);
+        if (hit) {
+            const int l = (int)__ffsll((long long)hit) - 1;
+            *b_out = b0 + l;
+            *c_out = id - __builtin_amdgcn_readlane(lo, l);
+            return true;
         }
     }
     return false;

@@ -42,7 +42,7 @@ struct KParams {
     int32_t adapt;        // library-chosen splits follow the actual lengths: 1 = the one sequence's, 2 = the batch's
     int32_t n_cu;         // compute units: the workgroup slots of one round
     int32_t item_slots;   // adapt == 2: (sequence, split) pairs the launched grid has room for
-    int32_t *dev_c;       // adapt == 2: the split size the split-KV pass derived, for the combine
+    int32_t *dev_c;       // adapt == 2: the batch plan (split size, pair count, pairs before each sequence)
     int32_t c_min;        // smallest split size the planner allows
     int32_t max_splits;
     int32_t RT;           // row tiles covering R
@@ -75,6 +75,7 @@ struct TimelineHook {
 TimelineHook timeline_hook();
 void set_timeline_hook(long long *buffer, long long capacity);
 hipError_t load_aux_kernels();
+hipError_t launch_batch_plan(const KParams &p, hipStream_t s);
 
 hipError_t launch_combine(const KParams &p, int D, bool half_partials, hipStream_t s);
 hipError_t launch_prepare(const int32_t *parent, const int32_t *ctx_lens, int B, int n, int32_t *parent2,

@@ -226,10 +226,10 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     // raw page-table entries of this split's window, the parent array, Q ----
     int C = p.C;                                      // revised below once the context length is known
     if (p.adapt == 2) {                               // a batch: the split size follows all its lengths
-        C = batch_split_tokens(p);
-        if (tid == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) *p.dev_c = C;
+        C = p.dev_c[0];                               // derived by the plan kernel that precedes this launch
+        C = min(max(C / kSplitQuantum, 1) * kSplitQuantum, p.C);
         // (y, z) is only a number here: the items that exist are the first ones in launch order
-        if (!batch_item(p, C, blockIdx.y + gridDim.y * blockIdx.z, &b, &c)) return;
+        if (!batch_item(p, blockIdx.y + gridDim.y * blockIdx.z, &b, &c)) return;
     }
     int pos0 = c * C;
     // drafted tokens of this sequence (a batch may mix tree sizes): rows of nodes >= Nb are

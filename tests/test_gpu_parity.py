@@ -411,9 +411,12 @@ def test_batch_split_follows_the_lengths(oracle_mod, name, ctx, Hkv):
     want = oracle_mod.verify_attn_case(case)
     got, step = _run(case)
     assert_close(got, want, case.dtype, name)
-    # the split size the kernels derived sits in the last 256 bytes of the workspace: a multiple of the
-    # 64-token stage, at most the planned size, and its (sequence, split) pairs fit the launched grid
-    c_dev = int(step.workspace[-256:-252].view(torch.int32).item())
+    # the batch plan sits at the end of the workspace (split size, pair count, pairs before each sequence):
+    # the size is a multiple of the 64-token stage, at most the planned one, and the pairs fit the launched grid
+    plan_bytes = -(-(4 * (len(ctx) + 3)) // 256) * 256
+    tail = step.workspace[-plan_bytes:].view(torch.int32).cpu().numpy()
+    c_dev = int(tail[0])
+    assert int(tail[1]) == sum(-(-(int(L) + n) // c_dev) for L in ctx) == int(tail[2 + len(ctx)])
     plan = step.plan
     assert c_dev % 64 == 0 and 64 <= c_dev <= plan.split_tokens
     pairs = sum(-(-(int(L) + n) // c_dev) for L in ctx)
