@@ -328,6 +328,26 @@ def test_measurement_aids():
     assert sorted(ran[:, 7]) == sorted(set(ran[:, 7]))
     assert (ran[:, 9] >= ran[:, 8]).all() and (ran[:, 8] > 0).all()   # shader cycles at both ends of the fast loop
 
+    # the split-KV launch with events attached to its dispatch: same result, a plausible duration
+    timer = B.KernelTimer()
+    step.out.fill_(float("nan"))
+    step.run_split_timed(timer)
+    step.run(phases=B.PHASE_COMBINE)
+    assert np.array_equal(step.result(), ref)
+    assert 1e-3 < timer.elapsed_ms() < 50.0
+
+    # the step probe: every wavefront reports its loop cycles, and the matrix pipe cannot be more than busy
+    src = torch.randn(8192, device="cuda").to(torch.bfloat16)
+    fs = torch.zeros(4 * 512, dtype=torch.float32, device="cuda")
+    cyc = torch.zeros(4 * 8, dtype=torch.int64, device="cuda")
+    for variant, _, tiles in B.STEP_PROBE_VARIANTS:
+        cyc.zero_()
+        B.owl_step_probe(variant, src, 200, fs, cyc, 4)
+        torch.cuda.synchronize()
+        per_step = cyc.cpu().numpy() / 200.0
+        assert (per_step > tiles * 17 * 16 * 0.5).all() and (per_step < 50000).all(), (variant, per_step)
+        assert np.isfinite(fs.cpu().numpy()).all()
+
 
 # ---------------------------------------------------------------------------
 # data errors on the device are flagged, never followed out of bounds
