@@ -592,6 +592,37 @@ def test_context_shorter_than_planned(oracle_mod, L, planned):
 
 
 # ---------------------------------------------------------------------------
+# the largest shapes the entry point takes
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("name,kw", [
+    # 64 drafted nodes x 8 query heads per KV head = 512 rows = 32 row tiles: two row groups of 24 + 8 tiles
+    ("n64_g8_tree", dict(dtype=W.DT_BF16, Hq=16, Hkv=2, D=128, ctx_lens=[20000], N=64, depth=8)),
+    # the same with fp16 storage and head_dim 64
+    ("n64_g8_f16_d64", dict(dtype=W.DT_F16, Hq=16, Hkv=2, D=64, ctx_lens=[9000, 1], N=64, depth=8)),
+    # 16 query heads on ONE KV head (multi-query attention), 24 row tiles exactly: three tiles on every wave
+    ("mqa_g16_n24", dict(dtype=W.DT_BF16, Hq=16, Hkv=1, D=128, ctx_lens=[15000], N=24, depth=6)),
+    # no grouping at all (Hq = Hkv), the deepest chain the mask word holds
+    ("mha_chain64", dict(dtype=W.DT_BF16, Hq=4, Hkv=4, D=128, ctx_lens=[5000, 33], N=64, depth=None)),
+    # a forest of 64 roots: every node sees only itself among the drafts
+    ("forest64", dict(dtype=W.DT_BF16, Hq=8, Hkv=2, D=128, ctx_lens=[3000], N=64, depth=0)),
+])
+def test_largest_shapes_every_element(oracle_mod, name, kw):
+    r = _rng(sum(map(ord, name)))                      # a fixed seed per case
+    N, depth = kw.pop("N"), kw.pop("depth")
+    def tree():
+        if depth is None:
+            return W.chain_tree(N)
+        if depth == 0:
+            return np.full(N, -1, np.int32)
+        return W.random_tree(N, depth, r)
+    case = W.make_case(name, 7000 + N, trees=[tree() for _ in kw["ctx_lens"]], **kw)
+    want = oracle_mod.verify_attn_case(case)
+    for split in (0, 1024):
+        got, step = _run(case, split_tokens=split)
+        assert_close(got, want, case.dtype, f"{name} split={split} plan={step.plan.as_dict()}")
+
+
+# ---------------------------------------------------------------------------
 # a context near the upper end: one million tokens, pools beyond 2^31 bytes
 # ---------------------------------------------------------------------------
 def test_million_token_context(oracle_mod):
