@@ -2,6 +2,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <atomic>
 #include <mutex>
 
 #include "owl_internal.h"
@@ -19,16 +20,16 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // so that planning stays usable for host-only checks.
 int device_cus()
 {
-    static int cached[16] = {0};
+    static std::atomic<int> cached[16];            // zero-initialised; callers may be on any thread
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return 256;
-    if (cached[dev] == 0) {
-        int n = 0;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
             n = 256;
-        cached[dev] = n;
+        cached[dev].store(n, std::memory_order_relaxed);
     }
-    return cached[dev];
+    return n;
 }
 
 owl_status check_desc(const owl_verify_desc *d)

@@ -2,7 +2,7 @@
 // measure what the chip can do (streaming reads, the matrix pipe), a one-wave
 // check of a cross-lane step, and the switch of the per-workgroup timeline
 // hook.  Declared in owl_probe.h; nothing here is on the product path.
-#include <atomic>
+#include <mutex>
 
 #include "owl_device.h"
 #include "owl_probe.h"
@@ -245,22 +245,20 @@ __global__ void __launch_bounds__(64) quad_max_kernel(const float *in, float *ou
 // The timeline hook's switch: a pointer and a capacity, read by the verify
 // entry points at launch time.
 // ---------------------------------------------------------------------------
-static std::atomic<long long *> g_tl_buffer{nullptr};
-static std::atomic<long long> g_tl_capacity{0};
+static std::mutex g_tl_mutex;
+static TimelineHook g_tl_hook = {nullptr, 0};
 
 TimelineHook timeline_hook()
 {
-    TimelineHook h;
-    h.capacity = g_tl_capacity.load(std::memory_order_acquire);
-    h.buffer = g_tl_buffer.load(std::memory_order_acquire);
-    return h;
+    std::lock_guard<std::mutex> lock(g_tl_mutex);    // pointer and capacity always belong together
+    return g_tl_hook;
 }
 
 void set_timeline_hook(long long *buffer, long long capacity)
 {
-    g_tl_buffer.store(nullptr, std::memory_order_release);       // never a pointer with the other buffer's size
-    g_tl_capacity.store(buffer ? capacity : 0, std::memory_order_release);
-    g_tl_buffer.store(buffer, std::memory_order_release);
+    std::lock_guard<std::mutex> lock(g_tl_mutex);
+    g_tl_hook.buffer = buffer;
+    g_tl_hook.capacity = buffer ? capacity : 0;
 }
 
 }  // namespace owl
