@@ -246,3 +246,66 @@ def test_commit_with_a_bad_page_moves_nothing_for_that_sequence():
             got = dev.cpu().numpy().view(pool.dtype).reshape(pool.shape)
             assert np.array_equal(got.view(np.uint8), want.view(np.uint8)), (which, name)
             assert np.array_equal(new_ctx.cpu().numpy(), want_ctx), which
+
+
+# --------------------------------------------------------------------------- the steps in a loop
+def test_decode_loop_stays_in_step_with_the_oracle():
+    """Five rounds of Prepare -> verify attention -> acceptance -> KV commit with every array
+    staying on the device between the calls (the tree, the accepted path, the new lengths and the
+    compacted cache of one call are the next call's inputs), against the same loop on the oracle:
+    integer state and cache bytes identical after every round, attention within the bf16 bound."""
+    import dataclasses
+    import oracle
+    r = _rng(2024)
+    n, rounds = 12, 5
+    N = 2 * n
+    start = np.array([37, 1000, 0, 16, 255], dtype=np.int32)
+    room = rounds * n                                                  # a round accepts at most n nodes
+    trees0 = [W.chain_tree(N) for _ in start]
+    cap = W.make_case("loop", 88, dtype=W.DT_BF16, Hq=8, Hkv=4, D=128, ctx_lens=(start + room).tolist(),
+                      trees=trees0, paged=True, head_major=True)
+    case = dataclasses.replace(cap, ctx_lens=start.copy())
+    step = VerifyStep(case, max_ctx_len=int(start.max()) + room)
+    Bn = case.B
+    p2 = torch.zeros((Bn, N), dtype=torch.int32, device=DEV)
+    anc = torch.zeros((Bn, N), dtype=torch.int64, device=DEV)
+    acc = torch.zeros((Bn, N), dtype=torch.int32, device=DEV)
+    na = torch.zeros(Bn, dtype=torch.int32, device=DEV)
+    bonus = torch.zeros(Bn, dtype=torch.int32, device=DEV)
+    last = torch.zeros(Bn, dtype=torch.int32, device=DEV)
+    ctx_dev = [step.ctx_lens, torch.zeros(Bn, dtype=torch.int32, device=DEV)]
+    k_o, v_o, ctx_o = case.k_pool, case.v_pool, start.copy()
+    strides = (case.stride_page, case.stride_head, case.stride_token, case.Hkv, case.D)
+    grew = 0
+    for it in range(rounds):
+        parents = np.stack([W.chain_tree(n) if b == it % Bn else W.random_tree(n, 4, r) for b in range(Bn)])
+        tok = r.integers(0, 2, size=(Bn, N))                           # two-word vocabulary: long accepted paths
+        tgt = r.integers(0, 2, size=(Bn, N))
+        root = r.integers(0, 2, size=Bn)
+        # oracle round
+        p2_o, *_ = S.prepare_spec_tree(parents, ctx_o)
+        ref = oracle.verify_attn_case(dataclasses.replace(case, k_pool=k_o, v_pool=v_o, ctx_lens=ctx_o,
+                                                          tree_parent=p2_o))
+        acc_o, na_o, bonus_o, last_o = S.accept_greedy(tok, p2_o, root, tgt, n)
+        k_o, ctx_n = S.commit_kv(k_o, case.page_table, ctx_o, acc_o, na_o, *strides)
+        v_o, _ = S.commit_kv(v_o, case.page_table, ctx_o, acc_o, na_o, *strides)
+        # device round: no host copies between the calls
+        cur, nxt = ctx_dev[it % 2], ctx_dev[(it + 1) % 2]
+        B.owl_prepare_spec_tree(_i32(parents), cur, p2, anc, None, None, step.status)
+        step.ctx_lens, step.tree_parent = cur, p2
+        step.run()
+        B.owl_accept_greedy(_i32(tok), p2, _i32(root), _i32(tgt), n, acc, na, bonus, last, step.status)
+        B.owl_commit_kv(step.desc, step.k, step.v, step.page_table, cur, acc, na, nxt, step.status)
+        out = step.result()
+        assert step.dev_status() == 0, it
+        assert np.array_equal(p2.cpu().numpy(), p2_o), it
+        assert np.abs(out - ref).max() < 1e-2 and np.abs(out - ref).mean() < 1e-3, (it, np.abs(out - ref).max())
+        assert np.array_equal(acc.cpu().numpy(), acc_o) and np.array_equal(na.cpu().numpy(), na_o), it
+        assert np.array_equal(bonus.cpu().numpy(), bonus_o) and np.array_equal(last.cpu().numpy(), last_o), it
+        assert np.array_equal(nxt.cpu().numpy(), ctx_n), it
+        for name, want, dev in (("k", k_o, step.k), ("v", v_o, step.v)):
+            got = dev.cpu().numpy().view(want.dtype).reshape(want.shape)
+            assert np.array_equal(got.view(np.uint8), want.view(np.uint8)), (it, name)
+        grew += int((ctx_n - ctx_o).sum())
+        ctx_o = ctx_n
+    assert grew > rounds                                               # the loop did move rows
