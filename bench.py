@@ -20,7 +20,8 @@ samples whatever --steps is) against whichever of the two roofs bounds the
 shape: 8 TB/s of HBM over the algorithmic K/V bytes or 2.5 PFLOP/s of dense
 bf16 MFMA over the algorithmic flop; both sides are printed.  `step_us` holds
 percentiles of single steps (an event after every step of a separate pass).
-`others` repeats this for the other bf16 workloads.  `cpu_baseline` times the
+`others` repeats this for the other bf16 workloads (timed over at least 200
+steps each: their steps are as short as 30 us).  `cpu_baseline` times the
 CPU oracle on a sample of output rows on this machine's host cores.
 """
 from __future__ import annotations
@@ -566,14 +567,17 @@ def roofline_of(case, t, workload):
     return r
 
 
-def bench_config(idx, args):
+def bench_config(idx, args, min_steps=0):
+    """`min_steps` (the `others` only): their steps are as short as 30 us, and the wall clock over the
+    headline's step count (20 steps = 0.6 ms) would mostly show how the host happened to be scheduled."""
     from paper_2510_07535_amd import workloads as W
     case = W.make_config(idx, dtype={"bf16": W.DT_BF16, "f16": W.DT_F16}[args.dtype])
     rot = Rotating(case, split_tokens=args.split_tokens)
-    t = rot.time_steps_with_kernel(args.steps, args.warmup, args.settle_ms)
+    steps = max(args.steps, min_steps)
+    t = rot.time_steps_with_kernel(steps, args.warmup, args.settle_ms)
     sec = t["step"]
     res = {
-        "workload": W.CONFIG_NAMES[idx], "config_index": idx,
+        "workload": W.CONFIG_NAMES[idx], "config_index": idx, "steps": steps,
         "us_per_step": sec * 1e6, "GBps": rot.kv_bytes / sec / 1e9,
         "frac_of_hbm_peak": rot.kv_bytes / sec / 1e9 / HBM_PEAK_GBS,
         "step_us": {"p10": t["step_p10"] * 1e6, "p50": t["step_p50"] * 1e6, "p90": t["step_p90"] * 1e6,
@@ -645,7 +649,7 @@ def main():
                 continue
             del rot
             torch.cuda.empty_cache()
-            _, rot, r = bench_config(idx, args)
+            _, rot, r = bench_config(idx, args, min_steps=200)
             others.append(r)
         line["others"] = others
     if args.all:
