@@ -62,3 +62,51 @@ def test_random_shape_matches_oracle(oracle_mod, seed):
     what = (f"seed {seed}: dtype {case.dtype} B {case.B} N {case.N} Hq {case.Hq} Hkv {case.Hkv} D {case.D} "
             f"ctx {case.ctx_lens.tolist()} split {split} plan {step.plan.as_dict()}")
     assert_close(got, want, case.dtype, what)
+
+
+def _draw_batch(seed):
+    """Medium-size batches for the split sizes the library chooses itself: mixed lengths (a quarter of the
+    sequences nearly empty), an announced maximum at or above the real one, sometimes per-sequence draft counts."""
+    r = np.random.Generator(np.random.Philox(key=77_000 + seed))
+    dtype = [W.DT_BF16, W.DT_BF16, W.DT_F16][int(r.integers(3))]
+    D = int(r.choice([64, 128, 128]))
+    Hkv = int(r.choice([1, 2, 4, 8]))
+    G = int(r.choice([1, 2, 4, 8]))
+    N = int(r.choice([1, 3, 6, 13, 26, 40, 60, 64]))
+    Bn = int(r.choice([1, 1, 2, 4, 9, 16, 33]))
+    top = int(r.choice([500, 5000, 20000]))
+    if Hkv * G * N > 1024 or Bn >= 9:
+        top = min(top, 5000)
+    ctx = [int(r.integers(0, top + 1)) if r.integers(4) else int(r.integers(0, 40)) for _ in range(Bn)]
+    trees = [W.random_tree(N, int(r.integers(2, 9)), r) if N > 1 and r.integers(3) else W.chain_tree(N)
+             for _ in range(Bn)]
+    case = W.make_case(f"batch{seed}", 900 + seed, dtype=dtype, Hq=Hkv * G, Hkv=Hkv, D=D, ctx_lens=ctx, trees=trees,
+                       paged=True, head_major=bool(r.integers(2)), spare_pages=int(r.integers(0, 3)))
+    planned = int(max(ctx) * float(r.choice([1.0, 1.0, 1.7, 4.0]))) + int(r.integers(0, 3))
+    counts = [int(r.integers(0, N + 1)) for _ in range(Bn)] if r.integers(3) == 0 else None
+    return case, max(planned, max(ctx)), counts
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_batch_through_the_library_plan(oracle_mod, seed):
+    import dataclasses
+    import torch
+    case, planned, counts = _draw_batch(seed)
+    cols = max((planned + case.N + 15) // 16, case.page_table.shape[1])   # the table covers the announced length
+    table = np.zeros((case.B, cols), dtype=np.int32)
+    table[:, :case.page_table.shape[1]] = case.page_table
+    wide = dataclasses.replace(case, page_table=table, max_pages_per_seq=cols)
+    step = VerifyStep(wide, max_ctx_len=planned, flags=B.OWL_FLAG_FP32_PARTIALS if seed % 2 else 0)
+    if counts is None:
+        step.run()
+        want = oracle_mod.verify_attn_case(case)
+    else:
+        nd = torch.tensor(counts, dtype=torch.int32, device=step.device)
+        B.owl_verify_attn_ragged(step.desc, step.q, step.k, step.v, step.page_table, step.ctx_lens,
+                                 step.tree_parent, nd, step.out, step.workspace, step.status)
+        want = oracle_mod.verify_attn_ragged_case(case, counts)
+    got = step.result()
+    assert step.dev_status() == 0
+    assert_close(got, want, case.dtype,
+                 f"seed {seed}: dtype {case.dtype} B {case.B} N {case.N} Hq {case.Hq} Hkv {case.Hkv} D {case.D} "
+                 f"ctx {case.ctx_lens.tolist()} announced {planned} counts {counts} plan {step.plan.as_dict()}")
