@@ -61,7 +61,7 @@ struct FullPlan {
     const Variant *variant;
     size_t part_o_bytes, part_ml_bytes, plan_bytes;
     bool half_partials;       // normalised fp16 partials (16-bit inputs unless the caller asks for fp32 ones)
-    int32_t adapt, c_min;
+    int32_t adapt, c_min, group_tiles;
     int64_t item_slots;       // adapt == 2: (sequence, split) pairs the grid has room for
     dim3 grid;                // of the split-KV pass
 };
@@ -73,23 +73,39 @@ owl_status make_plan(const owl_verify_desc *d, FullPlan *fp)
     const int G = d->n_q_heads / d->n_kv_heads;
     const int R = G * d->n_draft;
     const int RT = (R + kRowTile - 1) / kRowTile;
+    const int64_t T = (int64_t)d->max_ctx_len + d->n_draft;
+    int64_t cmin = align_up((size_t)(8 * R), kSplitQuantum);      // partials stay a small fraction of the K/V bytes
+    if (cmin < 256) cmin = 256;
     // Eight wavefronts per workgroup: WR of them split the row tiles, WK the
     // 32-key steps of a stage; a wave holds up to three tiles in accumulators.
-    int tpw, wr, wk, rgs;
+    // A workgroup takes up to 4 (WK = 2) or 8, 16, 24 (WK = 1) row tiles; more
+    // tiles than that go to further row groups, workgroups that read the same
+    // split.  Few KV streams (one or two KV heads of a tensor-parallel shard, one
+    // sequence) cannot fill the chip by splits alone without the partials
+    // outgrowing the K/V they summarise: then the rows are cut into more, smaller
+    // groups instead, each re-reading the split from its XCD's L2.
+    int tpw, wr, wk, rgs, group_tiles;
     if (d->qkv_dtype == OWL_F32) {
         tpw = 1; wr = 8; wk = 1; rgs = (RT + 7) / 8;
-    } else if (RT <= 4) {
-        tpw = 1; wr = 4; wk = 2; rgs = 1;
+        group_tiles = (RT + rgs - 1) / rgs;
     } else {
-        wr = 8; wk = 1;
-        rgs = (RT + 23) / 24;
-        const int per_wg = (RT + rgs - 1) / rgs;
-        tpw = (per_wg + 7) / 8;
+        static const int caps[4] = {24, 16, 8, 4};
+        int li = RT <= 4 ? 3 : (RT <= 8 ? 2 : (RT <= 16 ? 1 : 0));
+        const int64_t splits_at_most = d->split_tokens > 0
+            ? (T + (int64_t)align_up((size_t)d->split_tokens, kSplitQuantum) - 1) / (int64_t)align_up((size_t)d->split_tokens, kSplitQuantum)
+            : (T + cmin - 1) / cmin;
+        const int64_t streams = (int64_t)d->batch * d->n_kv_heads * (splits_at_most < 1 ? 1 : splits_at_most);
+        // (three quarters of the compute units will do: larger groups do more per K/V byte they read)
+        while (li < 3 && 4 * streams * ((RT + caps[li] - 1) / caps[li]) < 3 * (int64_t)device_cus()) ++li;
+        rgs = (RT + caps[li] - 1) / caps[li];
+        group_tiles = (RT + rgs - 1) / rgs;
+        rgs = (RT + group_tiles - 1) / group_tiles;
+        if (caps[li] == 4) { tpw = 1; wr = 4; wk = 2; }
+        else { wr = 8; wk = 1; tpw = (group_tiles + 7) / 8; }
     }
     const Variant *v = find_variant(d->qkv_dtype, d->head_dim, tpw, wr, wk);
     if (!v) return OWL_ERR_UNSUPPORTED;
-
-    const int64_t T = (int64_t)d->max_ctx_len + d->n_draft;
+    fp->group_tiles = group_tiles;
     int64_t C;
     if (d->split_tokens > 0) {
         C = align_up((size_t)d->split_tokens, kSplitQuantum);
@@ -101,11 +117,20 @@ owl_status make_plan(const owl_verify_desc *d, FullPlan *fp)
         const int64_t streams = (int64_t)d->batch * d->n_kv_heads * rgs;
         const int rounds = streams >= 64 ? 4 : 1;
         const int64_t want = (int64_t)device_cus() * rounds;      // one workgroup per CU at a time
+        // A single round must not spill a few workgroups into a second one.  With row groups the
+        // kernel keeps the groups of a (KV head, split) on one XCD, streams dealt round-robin over
+        // the eight XCDs: what has to fit is an XCD's share of the streams times the groups.
         int64_t S = (want + streams - 1) / streams;
+        if (rounds == 1) {
+            S = want / streams;
+            if (rgs > 1) {
+                const int64_t per_xcd = device_cus() / 8 / rgs;              // streams an XCD can hold at once
+                const int64_t heads = (int64_t)d->batch * d->n_kv_heads;
+                if (per_xcd >= 1 && 8 * per_xcd / heads >= 1) S = 8 * per_xcd / heads;
+            }
+        }
         if (S < 1) S = 1;
         C = align_up((size_t)((T + S - 1) / S), kSplitQuantum);
-        int64_t cmin = align_up((size_t)(8 * R), kSplitQuantum);
-        if (cmin < 256) cmin = 256;
         if (C < cmin) C = cmin;
     }
     if (C > kMaxSplitTokens) C = kMaxSplitTokens;
@@ -119,11 +144,7 @@ owl_status make_plan(const owl_verify_desc *d, FullPlan *fp)
     // k-and-a-bit rounds to k + 1 full ones never needs less than half the planned size,
     // so the grid and the partials are sized for splits of C / 2.
     fp->adapt = d->split_tokens != 0 ? 0 : (d->batch == 1 ? 1 : 2);
-    {
-        int64_t cmin = align_up((size_t)(8 * R), kSplitQuantum);
-        if (cmin < 256) cmin = 256;
-        fp->c_min = (int32_t)(cmin < C ? cmin : C);
-    }
+    fp->c_min = (int32_t)(cmin < C ? cmin : C);
     fp->item_slots = (int64_t)d->batch * max_splits;
     if (fp->adapt == 2) {
         // The device never asks for more pairs than the planned size gives at full length,
@@ -153,11 +174,18 @@ owl_status make_plan(const owl_verify_desc *d, FullPlan *fp)
     pl.kernel_variant = variant_index(v);
     // KV heads vary fastest (see the kernel's block-index comment); for a batch with a library-chosen
     // split size (y, z) merely number its (sequence, split) pairs densely
-    fp->grid = dim3(d->n_kv_heads * rgs, (unsigned)max_splits, d->batch);
+    // With row groups the kernel deals the workgroups out in units of eight (KV head, split, sequence)
+    // streams: the grid is padded so that their number is a multiple of 8 (the surplus exits at once).
+    int64_t grid_y = max_splits;
+    if (rgs > 1)
+        while (((int64_t)d->n_kv_heads * grid_y * d->batch) % 8 != 0) ++grid_y;
+    fp->grid = dim3(d->n_kv_heads * rgs, (unsigned)grid_y, d->batch);
     if (fp->adapt == 2) {
-        const int64_t per_z = fp->item_slots < 32768 ? fp->item_slots : 32768;
+        int64_t per_z = fp->item_slots < 32768 ? fp->item_slots : 32768;
+        if (rgs > 1) per_z = (per_z + 7) / 8 * 8;
         fp->grid = dim3(d->n_kv_heads * rgs, (unsigned)per_z, (unsigned)((fp->item_slots + per_z - 1) / per_z));
     }
+    if ((int64_t)fp->grid.x * fp->grid.y * fp->grid.z >= ((int64_t)1 << 31)) return OWL_ERR_UNSUPPORTED;   // the kernel numbers them in 32 bits
     pl.n_workgroups = (int32_t)((int64_t)fp->grid.x * fp->grid.y * fp->grid.z);
     fp->plan_bytes = align_up(((size_t)d->batch + 3) * sizeof(int32_t), 256);     // the batch plan
     pl.workspace_bytes = fp->part_o_bytes + fp->part_ml_bytes + fp->plan_bytes;
@@ -319,7 +347,7 @@ static owl_status verify_impl(const owl_verify_desc *desc, const void *q, const 
     p.C = fp.pub.split_tokens; p.max_splits = fp.pub.max_splits;
     p.adapt = fp.adapt; p.c_min = fp.c_min;
     p.n_cu = device_cus();
-    p.RT = fp.pub.row_tiles; p.row_groups = fp.pub.row_groups;
+    p.RT = fp.pub.row_tiles; p.row_groups = fp.pub.row_groups; p.group_tiles = fp.group_tiles;
     p.stride_page = desc->kv_stride_page; p.stride_head = desc->kv_stride_head;
     p.stride_token = desc->kv_stride_token; p.n_pool_pages = desc->n_pool_pages;
     p.c_log2 = desc->scale * 1.4426950408889634f;

@@ -47,6 +47,7 @@ struct KParams {
     int32_t max_splits;
     int32_t RT;           // row tiles covering R
     int32_t row_groups;
+    int32_t group_tiles;  // row tiles per row group (the last group may hold fewer)
     int64_t stride_page, stride_head, stride_token, n_pool_pages;
     float c_log2;         // scale * log2(e): scores live in the exp2 domain
     long long *timeline;  // instantiations with the timeline hook only: 10 slots per workgroup (profiling aid)

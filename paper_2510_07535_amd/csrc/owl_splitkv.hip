@@ -190,12 +190,24 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     // Workgroups go to the chip's eight XCDs round-robin in launch order, whether or not
     // they have work.  KV heads (all with the same amount of work) vary fastest, so that
     // splits that do not exist for a short sequence do not leave whole XCDs idle.
-    int c = blockIdx.y;
-    // Row groups that share a KV split (more than 24 row tiles) sit Hkv apart in x: with 8 KV
-    // heads they land on the same XCD at about the same time, and the second reads the split
-    // from that XCD's L2.
-    const int g = blockIdx.x % p.Hkv, rg = blockIdx.x / p.Hkv;
-    int b = blockIdx.z;
+    // n numbers the workgroups in launch order; a "stream" is one (KV head, split, sequence).
+    // Row groups (workgroups that take different row tiles of the same stream, each reading its
+    // K/V) are laid out so that the groups of a stream follow each other on ONE XCD: stream u sits
+    // on XCD u mod 8, its groups in consecutive slots of that XCD, and all but the first find the
+    // split in that XCD's L2.  With a single row group this is the plain order (n = u).
+    // (the host keeps the workgroup count of a launch below 2^31)
+    uint32_t n = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    int rg = 0;
+    if (p.row_groups > 1) {                          // the host pads the stream count to a multiple of 8
+        const uint32_t slot = n >> 3;
+        rg = (int)(slot % (uint32_t)p.row_groups);
+        n = ((slot / (uint32_t)p.row_groups) << 3) | (n & 7);
+    }
+    const int g = (int)(n % (uint32_t)p.Hkv);
+    const uint32_t item = n / (uint32_t)p.Hkv;       // (split, sequence), split fastest
+    int c = (int)(item % gridDim.y);
+    int b = (int)(item / gridDim.y);
+    if (p.adapt != 2 && b >= p.B) return;            // cannot happen with the grids the host launches
 
     // timeline of this workgroup (profiling instantiations only; the production kernels
     // carry neither the pointer nor a branch)
@@ -229,7 +241,7 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
         C = p.dev_c[0];                               // derived by the plan kernel that precedes this launch
         C = min(max(C / kSplitQuantum, 1) * kSplitQuantum, p.C);
         // (y, z) is only a number here: the items that exist are the first ones in launch order
-        if (!batch_item(p, blockIdx.y + gridDim.y * blockIdx.z, &b, &c)) return;
+        if (item >= (uint32_t)p.item_slots || !batch_item(p, (int)item, &b, &c)) return;
     }
     int pos0 = c * C;
     // drafted tokens of this sequence (a batch may mix tree sizes): rows of nodes >= Nb are
@@ -266,8 +278,8 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     auto load_queries = [&]() {
 #pragma unroll
     for (int t = 0; t < TPW; ++t) {
-        const int tg = rg * (WR * TPW) + t * WR + wr;
-        const bool tile_ok = tg < p.RT;
+        const int tg = rg * p.group_tiles + t * WR + wr;
+        const bool tile_ok = t * WR + wr < p.group_tiles && tg < p.RT;
         my_nt += tile_ok ? 1 : 0;
         const int row = tg * kRowTile + j;
         const bool ok = tile_ok && row < p.R && row / p.G < Nb;
@@ -1026,8 +1038,8 @@ __global__ void __launch_bounds__(kThreads) splitkv_kernel(const KParams p)
     if (wk == 0) {
 #pragma unroll
         for (int t = 0; t < TPW; ++t) {
-            const int tg = rg * (WR * TPW) + t * WR + wr;
-            if (tg >= p.RT) continue;
+            const int tg = rg * p.group_tiles + t * WR + wr;
+            if (t * WR + wr >= p.group_tiles || tg >= p.RT) continue;
             const size_t slot = (((size_t)b * p.Hkv + g) * p.max_splits + c) * p.RT + tg;
             const float l = O[t][NT][0];
             if (kF32 || !p.half_partials) {                          // uniform over the launch

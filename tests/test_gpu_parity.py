@@ -323,7 +323,8 @@ def test_measurement_aids():
     assert np.array_equal(got, ref)                      # recording does not change the result
     t = tl.cpu().numpy().reshape(nwg, 10)
     ran = t[t[:, 0] > 0]
-    assert len(ran) == 8 * ((3000 + 20 + 511) // 512)    # one workgroup per (kv head, split)
+    # one workgroup per (kv head, split, row group): 48 streams do not fill the chip, so the 5 row tiles go to 2 groups
+    assert step.plan.row_groups == 2 and len(ran) == 8 * ((3000 + 20 + 511) // 512) * step.plan.row_groups
     assert (np.diff(ran[:, :6], axis=1) >= 0).all()
     assert sorted(ran[:, 7]) == sorted(set(ran[:, 7]))
     assert (ran[:, 9] >= ran[:, 8]).all() and (ran[:, 8] > 0).all()   # shader cycles at both ends of the fast loop
@@ -620,6 +621,32 @@ def test_largest_shapes_every_element(oracle_mod, name, kw):
     for split in (0, 1024):
         got, step = _run(case, split_tokens=split)
         assert_close(got, want, case.dtype, f"{name} split={split} plan={step.plan.as_dict()}")
+
+
+# ---------------------------------------------------------------------------
+# one GPU's share of a model whose KV heads are spread over several GPUs
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("name,Hkv,G,N,L,groups,split,groups_at_split", [
+    ("70b_over_8_gpus", 1, 8, 40, 24000, 5, 1472, 5),     # 20 row tiles on one KV head: five row groups of four tiles
+    ("70b_over_4_gpus", 2, 8, 40, 24000, 5, 512, 3),      # two KV heads; with 47 splits: three groups of seven tiles
+    ("70b_over_4_gpus_b", 2, 8, 40, 24000, 5, 256, 2),    # with 94 splits: two groups of ten (two tiles per wave)
+    ("8b_over_8_gpus", 1, 4, 60, 12000, 4, 320, 4),       # 15 tiles: 4 + 4 + 4 + 3
+    ("wide_on_one_head", 1, 8, 64, 6000, 8, 1472, 8),     # 32 tiles on one head of a short context: eight groups
+])
+def test_few_kv_heads_use_row_groups(oracle_mod, name, Hkv, G, N, L, groups, split, groups_at_split):
+    """With one or two KV heads the splits alone cannot give every compute unit a workgroup: the rows
+    are cut into row groups (workgroups that read the same split).  Every element against the oracle,
+    with the library's own plan and with a forced split size that does not divide the context."""
+    r = _rng(sum(map(ord, name)))
+    case = W.make_case(name, 8100 + N, dtype=W.DT_BF16, Hq=Hkv * G, Hkv=Hkv, D=128, ctx_lens=[L],
+                       trees=[W.random_tree(N, 8, r)], outlier_frac=0.05)
+    want = oracle_mod.verify_attn_case(case)
+    got, step = _run(case)
+    assert step.plan.row_groups == groups, step.plan.as_dict()
+    assert_close(got, want, case.dtype, f"{name} plan={step.plan.as_dict()}")
+    got, step = _run(case, split_tokens=split)
+    assert step.plan.row_groups == groups_at_split, step.plan.as_dict()
+    assert_close(got, want, case.dtype, f"{name} split={split} plan={step.plan.as_dict()}")
 
 
 # ---------------------------------------------------------------------------
