@@ -72,6 +72,12 @@ def parse():
                     help="storage type of q/K/V (the configurations list bf16; f16 is the paper's type)")
     ap.add_argument("--drafter", action="store_true",
                     help="also time the drafter's recurrent cell (reported under 'drafter_cell'; implied by --all)")
+    ap.add_argument("--kv-head-shards", type=int, default=1,
+                    help="time ONE GPU's share of the --config workload when its KV heads (with their query heads) "
+                         "are spread over this many GPUs: the same lengths and tree on 1/N of the heads (still one GPU)")
+    ap.add_argument("--shard-shapes", action="store_true",
+                    help="also time one GPU's share of the 128K hybrid workload with its KV heads spread over 2, 4 and "
+                         "8 GPUs (reported under 'kv_head_shard_shapes'; implied by --all)")
     ap.add_argument("--draft-sweep", action="store_true",
                     help="also time a 64K-context step for 1..60 drafted tokens (reported under 'draft_count_sweep')")
     ap.add_argument("--evidence", action="store_true",
@@ -567,24 +573,24 @@ def roofline_of(case, t, workload):
     return r
 
 
-def bench_config(idx, args, min_steps=0):
+def bench_config(idx, args, min_steps=0, kv_shards=1):
     """`min_steps` (the `others` only): their steps are as short as 30 us, and the wall clock over the
     headline's step count (20 steps = 0.6 ms) would mostly show how the host happened to be scheduled."""
     from paper_2510_07535_amd import workloads as W
-    case = W.make_config(idx, dtype={"bf16": W.DT_BF16, "f16": W.DT_F16}[args.dtype])
+    case = W.make_config(idx, dtype={"bf16": W.DT_BF16, "f16": W.DT_F16}[args.dtype], kv_shards=kv_shards)
     rot = Rotating(case, split_tokens=args.split_tokens)
     steps = max(args.steps, min_steps)
     t = rot.time_steps_with_kernel(steps, args.warmup, args.settle_ms)
     sec = t["step"]
     res = {
-        "workload": W.CONFIG_NAMES[idx], "config_index": idx, "steps": steps,
+        "workload": W.CONFIG_NAMES[idx] if kv_shards == 1 else case.name, "config_index": idx, "steps": steps,
         "us_per_step": sec * 1e6, "GBps": rot.kv_bytes / sec / 1e9,
         "frac_of_hbm_peak": rot.kv_bytes / sec / 1e9 / HBM_PEAK_GBS,
         "step_us": {"p10": t["step_p10"] * 1e6, "p50": t["step_p50"] * 1e6, "p90": t["step_p90"] * 1e6,
                     "samples": t["step_samples"], "how": "an event after every step of a separate pass"},
         "kv_bytes": rot.kv_bytes, "plan": rot.step.plan.as_dict(), "kv_copies_rotated": len(rot.pools),
         "launches_per_step": 2,
-        "roofline": roofline_of(case, t, W.CONFIG_NAMES[idx]),
+        "roofline": roofline_of(case, t, W.CONFIG_NAMES[idx] if kv_shards == 1 else case.name),
     }
     assert rot.step.dev_status() == 0
     return case, rot, res
@@ -602,7 +608,7 @@ def main():
     B.lib()   # fail loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
-    case, rot, main_res = bench_config(args.config, args)
+    case, rot, main_res = bench_config(args.config, args, kv_shards=args.kv_head_shards)
     kbytes = main_res["kv_bytes"]
     line = {
         "metric": "verify-step attention: achieved HBM GB/s over algorithmic KV bytes (us per step in ms_per_step)",
@@ -645,7 +651,7 @@ def main():
     if not args.no_others:
         others = []
         for idx in (1, 2, 3, 4):
-            if idx == args.config:
+            if idx == args.config and args.kv_head_shards == 1:
                 continue
             del rot
             torch.cuda.empty_cache()
@@ -654,6 +660,15 @@ def main():
         line["others"] = others
     if args.all:
         line["step_kernels"] = bench_steps()
+    if args.all or args.shard_shapes:
+        shares = []
+        for n in (2, 4, 8):
+            del rot
+            torch.cuda.empty_cache()
+            _, rot, r = bench_config(3, args, min_steps=200, kv_shards=n)
+            r["kv_head_shards"] = n
+            shares.append(r)
+        line["kv_head_shard_shapes"] = shares
     if args.draft_sweep:
         line["draft_count_sweep"] = bench_draft_sweep()
     if args.all or args.drafter:

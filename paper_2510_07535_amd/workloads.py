@@ -273,13 +273,23 @@ def config_ctx_lens(idx: int, seed: Optional[int] = None) -> np.ndarray:
     raise ValueError(idx)
 
 
-def make_config(idx: int, seed: Optional[int] = None, ctx_scale: float = 1.0, dtype: Optional[int] = None) -> Case:
+def make_config(idx: int, seed: Optional[int] = None, ctx_scale: float = 1.0, dtype: Optional[int] = None,
+                kv_shards: int = 1) -> Case:
     """Configuration ``idx`` (0-based, in the order of the benchmark list).
     ``ctx_scale`` < 1 shrinks every context length by that factor (kept for
     CPU-sized parity runs of the same structure); 1.0 is the named size.
     ``dtype`` replaces the storage type of configurations 1..4 (bf16 as listed;
-    DT_F16 is the type the paper's runs used)."""
+    DT_F16 is the type the paper's runs used).  ``kv_shards`` > 1 gives one GPU's
+    share of the configuration when its KV heads (and their query heads) are
+    spread over that many GPUs: the same lengths and trees on 1/kv_shards of the heads."""
     seed = idx + 1 if seed is None else seed
+    if kv_shards > 1:
+        base = make_config(idx, seed, ctx_scale, dtype)
+        if idx == 0 or base.Hkv % kv_shards:
+            raise ValueError("kv_shards must divide the KV heads of configurations 1..4")
+        return make_case(f"{base.name}_heads1of{kv_shards}", seed, dtype=base.dtype, Hq=base.Hq // kv_shards,
+                         Hkv=base.Hkv // kv_shards, D=base.D, ctx_lens=base.ctx_lens,
+                         trees=list(base.tree_parent), outlier_frac=0.05 if idx == 3 else 0.0)
     if dtype is not None and idx > 0:
         base = make_config(idx, seed, ctx_scale)
         if dtype == base.dtype:
