@@ -78,6 +78,9 @@ def parse():
     ap.add_argument("--shard-shapes", action="store_true",
                     help="also time one GPU's share of the 128K hybrid workload with its KV heads spread over 2, 4 and "
                          "8 GPUs (reported under 'kv_head_shard_shapes'; implied by --all)")
+    ap.add_argument("--context-sweep", action="store_true",
+                    help="also time a 60-node tree (8B heads) and the 40-node hybrid tree (70B heads) on 4K..64K contexts "
+                         "(reported under 'context_sweep')")
     ap.add_argument("--draft-sweep", action="store_true",
                     help="also time a 64K-context step for 1..60 drafted tokens (reported under 'draft_count_sweep')")
     ap.add_argument("--evidence", action="store_true",
@@ -546,6 +549,29 @@ def bench_draft_sweep(ctx=65536, counts=(1, 4, 8, 16, 24, 32, 48, 60)):
     return out
 
 
+def bench_context_sweep(contexts=(4096, 8192, 16384, 32768, 65536)):
+    """Cost of one verify step against the context length (the benchmark's range starts at 4K tokens): 8B head shapes
+    with a 60-node tree, 70B head shapes with the 40-node hybrid tree, one sequence."""
+    import numpy as np
+    import torch
+    from paper_2510_07535_amd import workloads as W
+    rng = np.random.Generator(np.random.Philox(key=11))
+    out = []
+    for ctx in contexts:
+        for name, Hq, tree in (("8b_tree60", 32, W.random_tree(60, 6, rng)), ("70b_hybrid40", 64, W.hybrid_tree(32, 8, rng))):
+            case = W.make_case(f"{name}_{ctx // 1024}k", 4, dtype=W.DT_BF16, Hq=Hq, Hkv=8, D=128, ctx_lens=[ctx], trees=[tree])
+            rot = Rotating(case)
+            rot.settle(150)
+            sec = rot.time_steps(300, 20)
+            pl = rot.step.plan
+            out.append({"workload": case.name, "ctx": ctx, "rows_per_kv": pl.rows_per_kv, "us_per_step": sec * 1e6,
+                        "GBps": rot.kv_bytes / sec / 1e9, "split_tokens": pl.split_tokens, "row_groups": pl.row_groups,
+                        "tiles_per_wave": pl.tiles_per_wave, "n_workgroups": pl.n_workgroups})
+            del rot
+            torch.cuda.empty_cache()
+    return out
+
+
 def roofline_of(case, t, workload):
     """The split-KV kernel against both roofs; `bound` names the one with the longer floor."""
     kbytes = case.kv_bytes()
@@ -669,6 +695,8 @@ def main():
             r["kv_head_shards"] = n
             shares.append(r)
         line["kv_head_shard_shapes"] = shares
+    if args.context_sweep:
+        line["context_sweep"] = bench_context_sweep()
     if args.draft_sweep:
         line["draft_count_sweep"] = bench_draft_sweep()
     if args.all or args.drafter:

@@ -74,7 +74,8 @@ owl_status make_plan(const owl_verify_desc *d, FullPlan *fp)
     const int R = G * d->n_draft;
     const int RT = (R + kRowTile - 1) / kRowTile;
     const int64_t T = (int64_t)d->max_ctx_len + d->n_draft;
-    int64_t cmin = align_up((size_t)(8 * R), kSplitQuantum);      // partials stay a small fraction of the K/V bytes
+    // shortest split the planner uses: the fp16 partials of a split (R rows) stay below an eighth of the K/V it reads
+    int64_t cmin = align_up((size_t)(4 * R), kSplitQuantum);
     if (cmin < 256) cmin = 256;
     // Eight wavefronts per workgroup: WR of them split the row tiles, WK the
     // 32-key steps of a stage; a wave holds up to three tiles in accumulators.
@@ -113,7 +114,7 @@ owl_status make_plan(const owl_verify_desc *d, FullPlan *fp)
         // Enough workgroups to occupy every compute unit (several rounds when
         // many independent KV streams exist, which evens out ragged batches),
         // but splits long enough that the partials they write stay a small
-        // fraction of the K/V bytes they read (ratio ~ 2R / C).
+        // fraction of the K/V bytes they read (ratio ~ R / 2C with fp16 partials).
         const int64_t streams = (int64_t)d->batch * d->n_kv_heads * rgs;
         const int rounds = streams >= 64 ? 4 : 1;
         const int64_t want = (int64_t)device_cus() * rounds;      // one workgroup per CU at a time

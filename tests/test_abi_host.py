@@ -49,12 +49,14 @@ def test_plan_matches_shapes():
     assert p.split_tokens == 1024
     p = B.owl_verify_attn_plan(_good(n_draft=64, n_q_heads=64, max_ctx_len=131072, max_pages_per_seq=8200))   # 512 rows
     assert p.row_tiles == 32 and p.row_groups == 2 and p.tiles_per_wave == 2
-    # few KV streams: the rows go to more, smaller groups until the launch has a workgroup per compute unit
-    p = B.owl_verify_attn_plan(_good(n_draft=64, n_q_heads=64))        # the same rows on a 32K context
-    assert p.row_tiles == 32 and p.row_groups == 4 and p.tiles_per_wave == 1
+    # few KV streams: the rows go to more, smaller groups until the launch has about a workgroup per compute unit
+    p = B.owl_verify_attn_plan(_good(n_draft=64, n_q_heads=64, max_ctx_len=8192, max_pages_per_seq=520))   # 512 rows, 8K
+    assert p.row_tiles == 32 and p.row_groups == 8 and p.tiles_per_wave == 1
     p = B.owl_verify_attn_plan(_good(n_draft=40, n_q_heads=8, n_kv_heads=1, max_ctx_len=131072, max_pages_per_seq=8200))
-    assert p.row_tiles == 20 and p.row_groups == 5 and p.tiles_per_wave == 1 and 192 <= p.n_workgroups <= 256
-    assert p.n_workgroups % 8 == 0
+    assert p.row_tiles == 20 and p.row_groups == 2 and p.tiles_per_wave == 2 and 192 <= p.n_workgroups <= 256
+    assert p.n_workgroups % 8 == 0 and p.split_tokens >= 4 * 320
+    p = B.owl_verify_attn_plan(_good(n_draft=40, n_q_heads=8, n_kv_heads=1, max_ctx_len=24000, max_pages_per_seq=1510))
+    assert p.row_groups == 5 and p.tiles_per_wave == 1
 
 
 @pytest.mark.parametrize("over,code", [
