@@ -17,8 +17,9 @@ namespace owl {
 // channels of tiles u and u + 1; the weight of split s is then 2^(m_s - M) l_s s_s.
 //
 // One workgroup per (sequence, KV head, 16-row tile, pair of channel tiles);
-// its four waves take every fourth split, reduce their share against their own
-// running maximum, and are merged through LDS with the same formula.
+// its WAVES wavefronts (4, or 8 when there are more than 32 splits; 16 gained nothing) take every
+// WAVES-th split, reduce their share against their own running maximum, and are
+// merged through LDS with the same formula.
 // ---------------------------------------------------------------------------
 typedef _Float16 c_f16x2 __attribute__((ext_vector_type(2)));
 
@@ -28,8 +29,8 @@ __device__ __forceinline__ float2 unpack_half2(uint32_t w)
     return make_float2((float)h[0], (float)h[1]);
 }
 
-template <int D, bool HALF>
-__global__ void __launch_bounds__(256) combine_kernel(const KParams p)
+template <int D, bool HALF, int WAVES>
+__global__ void __launch_bounds__(64 * WAVES) combine_kernel(const KParams p)
 {
     constexpr int NT = D / 16, UPW = 2;              // channel tiles per workgroup
     constexpr int NUG = NT / UPW;
@@ -57,12 +58,12 @@ __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
     // partials of kInFlight splits are requested together, so that a wavefront pays the
     // memory latency once per batch rather than once per split (up to 32 splits: once).
     constexpr int kInFlight = 8;
-    for (int s0 = w; s0 < ns; s0 += 4 * kInFlight) {
+    for (int s0 = w; s0 < ns; s0 += WAVES * kInFlight) {
         float ms[kInFlight], ls[kInFlight], os[kInFlight];
         float4 x[kInFlight][UPW];
 #pragma unroll
         for (int k = 0; k < kInFlight; ++k) {
-            const int s = min(s0 + 4 * k, ns - 1);           // past the end: re-read the last split, not merged
+            const int s = min(s0 + WAVES * k, ns - 1);       // past the end: re-read the last split, not merged
             const size_t slot = slot0 + (size_t)s * p.RT;
             ms[k] = p.part_ml[slot * kPartMl + j];
             ls[k] = p.part_ml[slot * kPartMl + 16 + j];
@@ -81,7 +82,7 @@ __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
         }
 #pragma unroll
         for (int k = 0; k < kInFlight; ++k) {
-            if (s0 + 4 * k < ns) {                           // uniform over the wavefront
+            if (s0 + WAVES * k < ns) {                       // uniform over the wavefront
                 const float mn = fmaxf(mw, ms[k]);
                 const float a = __builtin_amdgcn_exp2f(mw - mn);     // 0 on the first round (mw = -inf)
                 const float c = __builtin_amdgcn_exp2f(ms[k] - mn);
@@ -96,21 +97,23 @@ __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
             }
         }
     }
-    __shared__ float4 s_acc[4][UPW][64];
-    __shared__ float s_m[4][64], s_l[4][64];
+    __shared__ float4 s_acc[WAVES][UPW][64];
+    __shared__ float s_m[WAVES][64], s_l[WAVES][64];
 #pragma unroll
     for (int u = 0; u < UPW; ++u) s_acc[w][u][lane] = acc[u];
     s_m[w][lane] = mw;
     s_l[w][lane] = lw;
     __syncthreads();
     if (w != 0) return;
-    float M = fmaxf(fmaxf(s_m[0][lane], s_m[1][lane]), fmaxf(s_m[2][lane], s_m[3][lane]));
+    float M = s_m[0][lane];
+#pragma unroll
+    for (int k = 1; k < WAVES; ++k) M = fmaxf(M, s_m[k][lane]);
     float lsum = 0.f;
     float4 tot[UPW];
 #pragma unroll
     for (int u = 0; u < UPW; ++u) tot[u] = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < WAVES; ++k) {
         const float wk = s_m[k][lane] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(s_m[k][lane] - M);
         lsum += wk * s_l[k][lane];
 #pragma unroll
@@ -132,13 +135,22 @@ __global__ void __launch_bounds__(256) combine_kernel(const KParams p)
                    p.out_dtype);
 }
 
+template <int WAVES>
+static void launch_combine_waves(const KParams &p, int D, bool half_partials, dim3 grid, hipStream_t s)
+{
+    const dim3 block(64 * WAVES);
+    if (D == 128 && half_partials) hipLaunchKernelGGL((combine_kernel<128, true, WAVES>), grid, block, 0, s, p);
+    else if (D == 128) hipLaunchKernelGGL((combine_kernel<128, false, WAVES>), grid, block, 0, s, p);
+    else if (half_partials) hipLaunchKernelGGL((combine_kernel<64, true, WAVES>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((combine_kernel<64, false, WAVES>), grid, block, 0, s, p);
+}
+
 hipError_t launch_combine(const KParams &p, int D, bool half_partials, hipStream_t s)
 {
     dim3 grid(p.RT * (D / 32), p.Hkv, p.B);
-    if (D == 128 && half_partials) hipLaunchKernelGGL((combine_kernel<128, true>), grid, dim3(256), 0, s, p);
-    else if (D == 128) hipLaunchKernelGGL((combine_kernel<128, false>), grid, dim3(256), 0, s, p);
-    else if (half_partials) hipLaunchKernelGGL((combine_kernel<64, true>), grid, dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((combine_kernel<64, false>), grid, dim3(256), 0, s, p);
+    // a wavefront merges its splits as a chain, 8 loads in flight: beyond 32 splits more wavefronts share them
+    if (p.max_splits > 32) launch_combine_waves<8>(p, D, half_partials, grid, s);
+    else launch_combine_waves<4>(p, D, half_partials, grid, s);
     return hipGetLastError();
 }
 
@@ -254,10 +266,15 @@ hipError_t launch_batch_plan(const KParams &p, hipStream_t s)
 hipError_t load_aux_kernels()
 {
     hipFuncAttributes a;
-    hipError_t e = hipFuncGetAttributes(&a, reinterpret_cast<const void *>(&combine_kernel<128, true>));
-    if (e == hipSuccess) e = hipFuncGetAttributes(&a, reinterpret_cast<const void *>(&combine_kernel<128, false>));
-    if (e == hipSuccess) e = hipFuncGetAttributes(&a, reinterpret_cast<const void *>(&combine_kernel<64, true>));
-    if (e == hipSuccess) e = hipFuncGetAttributes(&a, reinterpret_cast<const void *>(&combine_kernel<64, false>));
+    hipError_t e = hipSuccess;
+    const void *fns[] = {
+        reinterpret_cast<const void *>(&combine_kernel<128, true, 4>), reinterpret_cast<const void *>(&combine_kernel<128, false, 4>),
+        reinterpret_cast<const void *>(&combine_kernel<64, true, 4>), reinterpret_cast<const void *>(&combine_kernel<64, false, 4>),
+        reinterpret_cast<const void *>(&combine_kernel<128, true, 8>), reinterpret_cast<const void *>(&combine_kernel<128, false, 8>),
+        reinterpret_cast<const void *>(&combine_kernel<64, true, 8>), reinterpret_cast<const void *>(&combine_kernel<64, false, 8>),
+    };
+    for (const void *f : fns)
+        if (e == hipSuccess) e = hipFuncGetAttributes(&a, f);
     if (e == hipSuccess) e = hipFuncGetAttributes(&a, reinterpret_cast<const void *>(&batch_plan_kernel));
     return e;
 }
